@@ -1,0 +1,287 @@
+/*
+ * CPU reference for the routing math of GoodServe (predict-and-rectify
+ * request routing): TEST INFRASTRUCTURE ONLY.
+ *
+ * Nothing in the product path links, loads or calls this file; it exists so
+ * that the tests, the smoke check and the benchmark's CPU-baseline leg can
+ * compare the GPU library against a plain definition.  It shares no code,
+ * header, table or constant with the GPU library.
+ *
+ * What it is: every instance's continuous-batching queue is simulated one
+ * decode step at a time in fp64, and every request is scored against every
+ * instance by an exhaustive scan.  No sorting, no closed forms, no blocking.
+ *
+ *   - The end-to-end latency keeps the decomposition of Eq. 2 (Sec. 3.1):
+ *     queuing delay + prefill of the uncached prompt + decode time.
+ *   - The per-instance status (q_g, p_g, d_g), which Sec. 3.3 estimates
+ *     black-box, is here the white-box linear model the synthetic fleets are
+ *     defined with: prefill costs delta seconds per prompt token; one decode
+ *     step of a batch of B requests whose context lengths sum to C costs
+ *     alpha + beta*B + gamma*C seconds.
+ *   - Selection is Alg. 1 (Appendix, "Backend Selection Algorithm"): feasible
+ *     iff T <= D; among feasible instances the one with the largest d_g;
+ *     otherwise the one with the smallest T - D.  Ties go to the lowest
+ *     instance index.
+ *   - The risk re-check is Sec. 3.4, second half: a request is at risk when
+ *     its expected finish exceeds its deadline, and is then re-routed among
+ *     the other instances with the same rule; migration moves token IDs, so
+ *     the target prefills prompt + generated tokens again.
+ *
+ * Every function is pinned by tests that do not call it to produce their
+ * expectation: a pure-Python re-simulation with the request appended to the
+ * instance's queue, hand-worked values, closed forms of special cases and
+ * invariants of the model.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct gro_fleet {
+    int32_t n_inst, n_class;
+    double *delta, *alpha, *beta, *gamma; /* per class */
+    int32_t *inst_class;                  /* per instance */
+    double *q;                            /* queuing delay of instance g: all queued prefills */
+    double *d;                            /* duration of the instance's next decode step */
+    int32_t *smax;                        /* number of simulated steps of instance g */
+    double **w;                           /* w[g][s], s = 0..smax[g]: time of the first s steps */
+} gro_fleet;
+
+void gro_free(gro_fleet *f)
+{
+    if (!f) return;
+    if (f->w) for (int32_t g = 0; g < f->n_inst; ++g) free(f->w[g]);
+    free(f->w); free(f->smax); free(f->d); free(f->q); free(f->inst_class);
+    free(f->delta); free(f->alpha); free(f->beta); free(f->gamma);
+    free(f);
+}
+
+static double *dup_d(const double *src, size_t n)
+{
+    double *p = (double *)malloc(n * sizeof(double));
+    if (p) memcpy(p, src, n * sizeof(double));
+    return p;
+}
+
+/*
+ * Simulate one instance (Sec. 3.3's "batched serving mode", made explicit).
+ *
+ * Queued requests are prefilled back to back first (prefill has priority and
+ * stalls decoding, there is no batch-size cap); then every request of the
+ * instance decodes together.  One step emits one token for every batch member:
+ * its remaining length drops by one and its context grows by one; a request
+ * whose remaining length reaches zero finishes at the end of that step.
+ * Times are measured from now = 0.
+ */
+static int simulate_instance(double delta, double alpha, double beta, double gamma,
+                             int32_t n_act, const int32_t *a_prompt, const int32_t *a_gen,
+                             const int32_t *a_rem,
+                             int32_t n_q, const int32_t *q_prompt, const int32_t *q_len,
+                             double *a_finish, double *q_finish,
+                             double *q_out, double *d_out, int32_t *smax_out, double **w_out)
+{
+    int32_t n = n_act + n_q;
+    int32_t *rem = (int32_t *)malloc((size_t)(n ? n : 1) * sizeof(int32_t));
+    int64_t *ctx = (int64_t *)malloc((size_t)(n ? n : 1) * sizeof(int64_t));
+    int32_t *who = (int32_t *)malloc((size_t)(n ? n : 1) * sizeof(int32_t));
+    if (!rem || !ctx || !who) { free(rem); free(ctx); free(who); return -1; }
+
+    double t = 0.0;
+    int32_t smax = 0;
+    for (int32_t j = 0; j < n_q; ++j) {          /* queued: prefill, then join the batch */
+        t += delta * (double)q_prompt[j];
+        rem[n_act + j] = q_len[j];
+        ctx[n_act + j] = q_prompt[j];
+        who[n_act + j] = n_act + j;
+    }
+    double q = t;
+    for (int32_t i = 0; i < n_act; ++i) {        /* actives are already in the batch */
+        rem[i] = a_rem[i];
+        ctx[i] = (int64_t)a_prompt[i] + a_gen[i];
+        who[i] = i;
+    }
+    for (int32_t j = 0; j < n; ++j) if (rem[j] > smax) smax = rem[j];
+
+    double *w = (double *)malloc((size_t)(smax + 1) * sizeof(double));
+    if (!w) { free(rem); free(ctx); free(who); return -1; }
+    w[0] = 0.0;
+
+    /* the instance's decode step time right now; an idle instance would take alpha */
+    {
+        int64_t c = 0;
+        for (int32_t j = 0; j < n; ++j) c += ctx[j];
+        *d_out = fma(gamma, (double)c, fma(beta, (double)n, alpha));
+    }
+
+    int32_t nb = n, s = 0;
+    double elapsed = 0.0;                        /* decode time since q */
+    while (nb > 0) {
+        int64_t c = 0;
+        for (int32_t j = 0; j < nb; ++j) c += ctx[j];
+        double step = fma(gamma, (double)c, fma(beta, (double)nb, alpha));
+        elapsed += step;
+        ++s;
+        w[s] = elapsed;
+        int32_t m = 0;
+        for (int32_t j = 0; j < nb; ++j) {
+            rem[j] -= 1;
+            ctx[j] += 1;
+            if (rem[j] <= 0) {
+                double fin = q + elapsed;
+                if (who[j] < n_act) { if (a_finish) a_finish[who[j]] = fin; }
+                else if (q_finish) q_finish[who[j] - n_act] = fin;
+            } else {
+                rem[m] = rem[j]; ctx[m] = ctx[j]; who[m] = who[j]; ++m;
+            }
+        }
+        nb = m;
+    }
+    *q_out = q;
+    *smax_out = s;
+    *w_out = w;
+    free(rem); free(ctx); free(who);
+    return 0;
+}
+
+/*
+ * Simulate every instance; returns a handle holding q_g, d_g and the step
+ * table of each instance, and writes each request's expected finish time.
+ * a_finish / q_finish may be NULL.  All arrays are host arrays; act_off and
+ * q_off are CSR offsets of length n_inst + 1.
+ */
+gro_fleet *gro_simulate(int32_t n_inst, int32_t n_class,
+                        const double *delta, const double *alpha,
+                        const double *beta, const double *gamma,
+                        const int32_t *inst_class,
+                        const int32_t *act_off, const int32_t *act_prompt,
+                        const int32_t *act_gen, const int32_t *act_rem,
+                        const int32_t *q_off, const int32_t *q_prompt, const int32_t *q_len,
+                        double *a_finish, double *q_finish)
+{
+    gro_fleet *f = (gro_fleet *)calloc(1, sizeof(gro_fleet));
+    if (!f) return NULL;
+    f->n_inst = n_inst; f->n_class = n_class;
+    f->delta = dup_d(delta, n_class); f->alpha = dup_d(alpha, n_class);
+    f->beta = dup_d(beta, n_class);   f->gamma = dup_d(gamma, n_class);
+    f->inst_class = (int32_t *)malloc((size_t)(n_inst ? n_inst : 1) * sizeof(int32_t));
+    f->q = (double *)calloc((size_t)(n_inst ? n_inst : 1), sizeof(double));
+    f->d = (double *)calloc((size_t)(n_inst ? n_inst : 1), sizeof(double));
+    f->smax = (int32_t *)calloc((size_t)(n_inst ? n_inst : 1), sizeof(int32_t));
+    f->w = (double **)calloc((size_t)(n_inst ? n_inst : 1), sizeof(double *));
+    if (!f->delta || !f->alpha || !f->beta || !f->gamma || !f->inst_class ||
+        !f->q || !f->d || !f->smax || !f->w) { gro_free(f); return NULL; }
+    memcpy(f->inst_class, inst_class, (size_t)n_inst * sizeof(int32_t));
+
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t g = 0; g < n_inst; ++g) {
+        int c = inst_class[g];
+        int32_t a0 = act_off[g], q0 = q_off[g];
+        int rc = simulate_instance(delta[c], alpha[c], beta[c], gamma[c],
+                                   act_off[g + 1] - a0, act_prompt + a0, act_gen + a0, act_rem + a0,
+                                   q_off[g + 1] - q0, q_prompt + q0, q_len + q0,
+                                   a_finish ? a_finish + a0 : NULL, q_finish ? q_finish + q0 : NULL,
+                                   &f->q[g], &f->d[g], &f->smax[g], &f->w[g]);
+        if (rc) {
+#pragma omp atomic write
+            failed = 1;
+        }
+    }
+    if (failed) { gro_free(f); return NULL; }
+    return f;
+}
+
+void gro_status(const gro_fleet *f, double *q, double *d, int32_t *smax)
+{
+    for (int32_t g = 0; g < f->n_inst; ++g) {
+        if (q) q[g] = f->q[g];
+        if (d) d[g] = f->d[g];
+        if (smax) smax[g] = f->smax[g];
+    }
+}
+
+/* copy of instance g's step table, w[0..smax] */
+void gro_step_table(const gro_fleet *f, int32_t g, double *w)
+{
+    memcpy(w, f->w[g], (size_t)(f->smax[g] + 1) * sizeof(double));
+}
+
+/*
+ * Eq. 2 for one (request, instance) pair.  The request waits q_g, prefills
+ * its own c0 tokens (H = 0 cached), then takes len decode steps in a batch
+ * that holds it and whoever of the instance's requests is still running: the
+ * first len step times of the instance, plus what its own presence adds to
+ * each of them (one more batch member, its context c0 + s - 1 at step s).
+ * Past the instance's last request only the new request is left.
+ */
+static double pair_T(const gro_fleet *f, int32_t g, int64_t c0, int64_t len)
+{
+    int c = f->inst_class[g];
+    double alpha = f->alpha[c], beta = f->beta[c], gamma = f->gamma[c], delta = f->delta[c];
+    int32_t smax = f->smax[g];
+    double base = (len <= smax) ? f->w[g][len]
+                                : f->w[g][smax] + (double)(len - smax) * alpha;
+    double tri = (double)(len * (len - 1) / 2);
+    double own = beta * (double)len + gamma * ((double)(c0 * len) + tri);
+    return f->q[g] + delta * (double)c0 + base + own;
+}
+
+/* T for every pair: out[r * n_inst + g] */
+void gro_pair_T(const gro_fleet *f, int64_t n_req, const int32_t *c0, const int32_t *len,
+                double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < n_req; ++r)
+        for (int32_t g = 0; g < f->n_inst; ++g)
+            out[r * f->n_inst + g] = pair_T(f, g, c0[r], len[r]);
+}
+
+/*
+ * Alg. 1 for a batch, every request against the same snapshot of the fleet.
+ * exclude (may be NULL) names an instance a request may not be sent to
+ * (-1: none).  out_inst = -1 when no instance is allowed at all.
+ */
+void gro_route(const gro_fleet *f, int64_t n_req, const int32_t *c0, const int32_t *len,
+               const double *deadline, const int32_t *exclude,
+               int32_t *out_inst, double *out_slack, uint8_t *out_fallback, double *out_T)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < n_req; ++r) {
+        int32_t ex = exclude ? exclude[r] : -1;
+        double D = deadline[r];
+        int32_t best_feas = -1, best_any = -1;
+        double best_feas_d = 0.0, best_feas_T = 0.0, best_any_T = 0.0;
+        for (int32_t g = 0; g < f->n_inst; ++g) {
+            if (g == ex) continue;
+            double T = pair_T(f, g, c0[r], len[r]);
+            if (T <= D) {
+                if (best_feas < 0 || f->d[g] > best_feas_d) {
+                    best_feas = g; best_feas_d = f->d[g]; best_feas_T = T;
+                }
+            }
+            if (best_any < 0 || T < best_any_T) { best_any = g; best_any_T = T; }
+        }
+        int32_t pick = best_feas >= 0 ? best_feas : best_any;
+        double T = best_feas >= 0 ? best_feas_T : best_any_T;
+        out_inst[r] = pick;
+        if (out_slack) out_slack[r] = pick >= 0 ? D - T : 0.0;
+        if (out_fallback) out_fallback[r] = (uint8_t)(best_feas < 0);
+        if (out_T) out_T[r] = pick >= 0 ? T : 0.0;
+    }
+}
+
+int32_t gro_threads(void)
+{
+    int32_t n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp single
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

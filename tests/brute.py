@@ -1,0 +1,54 @@
+"""Pure-Python brute force used only to pin the CPU reference on tiny inputs.
+
+Written apart from ``oracle/`` on purpose: a request's latency on an instance
+is found by *putting the request on the instance* (last in its queue) and
+replaying the whole instance one decode step at a time with Python floats,
+so it knows nothing of step tables or of the separable "own" term.  Selection
+is Alg. 1 spelled out with Python lists.
+"""
+from __future__ import annotations
+
+
+def replay(coef, active, queued):
+    """coef = (delta, alpha, beta, gamma); active = [(prompt, gen, rem)];
+    queued = [(prompt, len)].  Returns (q, first_step, finish list in the
+    order actives then queued)."""
+    delta, alpha, beta, gamma = coef
+    t = 0.0
+    batch = []
+    for i, (p, g, r) in enumerate(active):
+        batch.append({"id": i, "rem": r, "ctx": p + g})
+    for j, (p, l) in enumerate(queued):
+        t += delta * p
+        batch.append({"id": len(active) + j, "rem": l, "ctx": p})
+    q = t
+    finish = [None] * len(batch)
+    first = alpha + beta * len(batch) + gamma * sum(b["ctx"] for b in batch)
+    while batch:
+        t += alpha + beta * len(batch) + gamma * sum(b["ctx"] for b in batch)
+        for b in batch:
+            b["rem"] -= 1
+            b["ctx"] += 1
+            if b["rem"] == 0:
+                finish[b["id"]] = t
+        batch = [b for b in batch if b["rem"] > 0]
+    return q, first, finish
+
+
+def latency_if_routed(coef, active, queued, c0, length):
+    """T(r, g) by definition: append r behind the queue and replay."""
+    _, _, finish = replay(coef, active, list(queued) + [(c0, length)])
+    return finish[-1]
+
+
+def select(T, d, deadline, exclude=-1):
+    """Alg. 1: feasible set, largest d_g among it, else smallest violation."""
+    cand = [g for g in range(len(T)) if g != exclude]
+    if not cand:
+        return -1, True
+    feas = [g for g in cand if T[g] <= deadline]
+    if feas:
+        best = max(d[g] for g in feas)
+        return min(g for g in feas if d[g] == best), False
+    best = min(T[g] - deadline for g in cand)
+    return min(g for g in cand if T[g] - deadline == best), True
