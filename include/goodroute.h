@@ -1,0 +1,184 @@
+/*
+ * libgoodroute: the batched routing math of GoodServe's predict-and-rectify
+ * request router, for one AMD MI355X (gfx950).
+ *
+ * The three calls follow the paper's statement of the routing problem:
+ *
+ *   gr_build_status  the per-instance status that Eq. 2 (Sec. 3.1) needs (queuing
+ *                    delay q_g, decode speed d_g) and the expected end-to-end
+ *                    finish time of every request an instance already holds;
+ *   gr_score_route   Alg. 1 ("Backend Selection Algorithm", Appendix) for a
+ *                    batch of incoming requests: T(r,g) of Eq. 2 for every
+ *                    (request, instance) pair, feasibility T <= D_r, the
+ *                    just-enough choice of Sec. 3.4, the least-violation
+ *                    fallback;
+ *   gr_risk_scan     the periodic SLO-violation re-check of Sec. 3.4 over all
+ *                    active requests, with a just-enough migration target for
+ *                    every request found at risk.
+ *
+ * Time model.  Sec. 3.3 estimates q_g, p_g, d_g black-box; this library takes
+ * them from an explicit model of a continuously batching instance of GPU
+ * class c:  prefill costs delta_c seconds per prompt token, and one decode
+ * step of a batch of B requests whose context lengths sum to C costs
+ * alpha_c + beta_c*B + gamma_c*C seconds.  Queued requests are prefilled back
+ * to back before decoding resumes; every step emits one token per batch
+ * member.  "Now" is time 0 of every call.
+ *
+ * Conventions.  Every function returns GR_OK (0) or a negative GR_ERR_* code;
+ * nothing throws or aborts.  Pointers marked DEVICE are device memory owned by
+ * the caller (readable/writable by kernels on the current device); pointers
+ * marked HOST are ordinary host memory read during the call.  Work is queued
+ * on the given HIP stream (a hipStream_t passed as void*, NULL = default
+ * stream) and the calls do not wait for it; outputs are valid once the stream
+ * has been synchronised.  The handle owns its tables and workspace, sized at
+ * gr_create; no call after gr_create allocates.  Calls on one handle must not
+ * overlap.  Token counts are int32; times are seconds.
+ *
+ * Input contract for device data (not validated on the host): remaining and
+ * predicted lengths in [1, max_len]; prompt >= 1; generated >= 0; entries per
+ * instance <= max_entries_per_inst; CSR offsets non-decreasing, starting at 0.
+ * Kernels stay in bounds when the contract is broken (lengths are clamped,
+ * surplus entries dropped) and raise a sticky bit readable with
+ * gr_device_status.
+ */
+#ifndef GOODROUTE_H
+#define GOODROUTE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gr_fleet gr_fleet;
+
+enum {
+    GR_OK = 0,
+    GR_ERR_INVALID_ARG = -1, /* NULL where a pointer is required, negative size, bad class id */
+    GR_ERR_TOO_LARGE = -2,   /* a size exceeds what the handle was created for, or a hard limit */
+    GR_ERR_HIP = -3,         /* a HIP runtime call failed */
+    GR_ERR_NO_STATUS = -4,   /* gr_score_route before any gr_build_status / gr_risk_scan */
+    GR_ERR_NOMEM = -5        /* host or device allocation failed in gr_create */
+};
+
+/* bits of gr_device_status */
+enum {
+    GR_DEV_LEN_CLAMPED = 1,   /* a length outside [0, max_len] was clamped */
+    GR_DEV_ENTRIES_DROPPED = 2 /* an instance held more than max_entries_per_inst entries */
+};
+
+/*
+ * Create a fleet handle on the current HIP device.
+ *   n_inst, n_class           M instances of n_class GPU classes (n_class <= 64)
+ *   delta, alpha, beta, gamma HOST, n_class doubles each, all >= 0: the model above
+ *   inst_class                HOST, n_inst class ids in [0, n_class)
+ *   max_entries_per_inst      upper bound of active + queued requests on one instance
+ *   max_len                   upper bound of any remaining / predicted decode length
+ *   max_requests              upper bound of n_req of one gr_score_route call
+ * Hard limits: bits(max_len) + bits(max_entries_per_inst) <= 32 (a length and
+ * an entry index share one sort word); max_entries_per_inst <= 8192.
+ */
+int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
+              const double* delta, const double* alpha, const double* beta, const double* gamma,
+              const int32_t* inst_class,
+              int32_t max_entries_per_inst, int32_t max_len, int64_t max_requests);
+
+/* Free the handle and its device memory (waits for the device first). NULL is allowed. */
+int gr_destroy(gr_fleet* f);
+
+/*
+ * Step 1 (Eq. 2's per-instance terms; "expected finish time" of Sec. 3.4).
+ * For every instance: q_g = delta * (sum of queued prompts); the requests it
+ * holds are ordered by remaining length, which turns the step-by-step run of
+ * its batch into a closed form; out come the finish time of every request,
+ * d_g = duration of the instance's next decode step (alpha for an idle
+ * instance), the capability rank used by Alg. 1's argmax d_g, and the
+ * instance tables kept in the handle for gr_score_route.
+ *
+ *   act_off        DEVICE int32[n_inst+1]  CSR offsets of active requests by instance
+ *   act_prompt     DEVICE int32[n_active]  prompt tokens
+ *   act_gen        DEVICE int32[n_active]  tokens generated so far
+ *   act_rem        DEVICE int32[n_active]  predicted remaining decode length
+ *   q_off          DEVICE int32[n_inst+1]  CSR offsets of queued requests by instance
+ *   q_prompt,q_len DEVICE int32[n_queued]  prompt tokens, predicted decode length
+ *   n_active, n_queued                     array lengths (host values)
+ *   out_act_finish DEVICE float[n_active]  expected finish time, same order as inputs
+ *   out_q_finish   DEVICE float[n_queued]  may be NULL
+ *   out_d          DEVICE double[n_inst]   may be NULL
+ *   out_rank       DEVICE int32[n_inst]    may be NULL; 0 = largest d_g, ties by index
+ */
+int gr_build_status(gr_fleet* f,
+                    const int32_t* act_off, const int32_t* act_prompt,
+                    const int32_t* act_gen, const int32_t* act_rem, int64_t n_active,
+                    const int32_t* q_off, const int32_t* q_prompt, const int32_t* q_len,
+                    int64_t n_queued,
+                    float* out_act_finish, float* out_q_finish,
+                    double* out_d, int32_t* out_rank, void* hip_stream);
+
+/*
+ * Step 2 (Alg. 1 on a batch; every request is scored against the same
+ * snapshot: the tables of the last gr_build_status / gr_risk_scan).
+ * A request that goes to instance g waits q_g, prefills its ctx0 tokens
+ * (no cached prefix), then decodes pred_len steps in g's batch:
+ *   T(r,g) = q_g + delta*ctx0 + [time of g's next pred_len steps with r in the batch].
+ * Feasible iff T <= budget.  Choice: the feasible instance with the largest
+ * d_g (ties: lowest index); if none, the instance with the smallest T (ties:
+ * lowest index).
+ *
+ *   n_req          number of requests (0 allowed)
+ *   ctx0           DEVICE int32[n_req]  tokens to prefill (prompt; prompt+generated when migrating)
+ *   pred_len       DEVICE int32[n_req]  predicted decode length
+ *   budget         DEVICE float[n_req]  D_r, seconds from now
+ *   exclude_inst   DEVICE int32[n_req]  instance a request may not go to, -1 none; may be NULL
+ *   out_inst       DEVICE int32[n_req]  chosen instance (-1 if every instance is excluded)
+ *   out_slack      DEVICE float[n_req]  budget - T(r, chosen)
+ *   out_fallback   DEVICE uint8[n_req]  1 if no instance was feasible; may be NULL
+ *   out_T          DEVICE float[n_req*n_inst], row-major; may be NULL. Every pair's
+ *                  T, for checking; costs 4 bytes of traffic per pair.
+ */
+int gr_score_route(gr_fleet* f, int64_t n_req,
+                   const int32_t* ctx0, const int32_t* pred_len, const float* budget,
+                   const int32_t* exclude_inst,
+                   int32_t* out_inst, float* out_slack, uint8_t* out_fallback,
+                   float* out_T, void* hip_stream);
+
+/*
+ * Step 3 (Sec. 3.4, periodic re-check).  Rebuilds the status from refreshed
+ * remaining lengths (as gr_build_status, replacing the handle's tables), flags
+ * every active request whose expected finish exceeds its budget
+ * (finish > budget, compared in fp64), and for every flagged request runs
+ * Alg. 1 over all other instances with ctx0 = prompt + generated (migration
+ * moves token IDs, the target prefills them again), pred_len = its refreshed
+ * remaining length and D = its budget.  Targets are scored against the
+ * refreshed snapshot, the request still counted where it runs now.
+ *
+ *   act_budget       DEVICE float[n_active]  arrival + SLO - now (may be negative)
+ *   out_flag         DEVICE uint8[n_active]
+ *   out_finish       DEVICE float[n_active]
+ *   out_target       DEVICE int32[n_active]  -1 if not flagged (or no other instance)
+ *   out_target_slack DEVICE float[n_active]  0 if not flagged
+ *   out_n_flagged    DEVICE int32[1]         may be NULL
+ */
+int gr_risk_scan(gr_fleet* f,
+                 const int32_t* act_off, const int32_t* act_prompt,
+                 const int32_t* act_gen, const int32_t* act_rem_refreshed, int64_t n_active,
+                 const int32_t* q_off, const int32_t* q_prompt, const int32_t* q_len,
+                 int64_t n_queued,
+                 const float* act_budget,
+                 uint8_t* out_flag, float* out_finish,
+                 int32_t* out_target, float* out_target_slack, int32_t* out_n_flagged,
+                 void* hip_stream);
+
+/*
+ * Synchronises the device and returns the OR of the GR_DEV_* bits raised by
+ * kernels since gr_create (HOST int32 out).  Not for the hot path.
+ */
+int gr_device_status(gr_fleet* f, int32_t* out_bits);
+
+/* Static, human-readable text for a return code. */
+const char* gr_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GOODROUTE_H */

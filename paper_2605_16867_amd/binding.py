@@ -1,0 +1,149 @@
+"""ctypes binding of libgoodroute: same names as the C interface, argument
+marshalling only.  Tensors are torch tensors on the GPU (device memory and the
+current stream come from torch; every step of the path runs in the library's
+kernels).  There is no fallback: without the built library every call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "csrc", "libgoodroute.so")
+
+EXPORTS = ("gr_create", "gr_destroy", "gr_build_status", "gr_score_route", "gr_risk_scan",
+           "gr_device_status", "gr_strerror")
+
+_lib = None
+
+
+class GoodRouteError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+def lib() -> C.CDLL:
+    """Load libgoodroute.so (built by paper_2605_16867_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2605_16867_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        p, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+        l.gr_create.restype = C.c_int
+        l.gr_create.argtypes = [C.POINTER(p), i32, i32, p, p, p, p, p, i32, i32, i64]
+        l.gr_destroy.restype = C.c_int
+        l.gr_destroy.argtypes = [p]
+        l.gr_build_status.restype = C.c_int
+        l.gr_build_status.argtypes = [p, p, p, p, p, i64, p, p, p, i64, p, p, p, p, p]
+        l.gr_score_route.restype = C.c_int
+        l.gr_score_route.argtypes = [p, i64, p, p, p, p, p, p, p, p, p]
+        l.gr_risk_scan.restype = C.c_int
+        l.gr_risk_scan.argtypes = [p, p, p, p, p, i64, p, p, p, i64, p, p, p, p, p, p, p]
+        l.gr_device_status.restype = C.c_int
+        l.gr_device_status.argtypes = [p, C.POINTER(i32)]
+        l.gr_strerror.restype = C.c_char_p
+        l.gr_strerror.argtypes = [C.c_int]
+        _lib = l
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().gr_strerror(int(code)).decode()
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        raise GoodRouteError(code, where)
+
+
+def _dev(t, dtype, name: str, n: Optional[int] = None):
+    """Device pointer of a contiguous GPU tensor of the given dtype (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: need a contiguous {dtype} GPU tensor, got {t.dtype} on {t.device}")
+    if n is not None and t.numel() < n:
+        raise ValueError(f"{name}: {t.numel()} elements, need {n}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Fleet:
+    """Owns a gr_fleet handle on the current device."""
+
+    def __init__(self, delta, alpha, beta, gamma, inst_class, max_entries_per_inst: int,
+                 max_len: int, max_requests: int):
+        import numpy as np
+        self._h = C.c_void_p()
+        co = [np.ascontiguousarray(x, dtype=np.float64) for x in (delta, alpha, beta, gamma)]
+        ic = np.ascontiguousarray(inst_class, dtype=np.int32)
+        self.n_inst = int(ic.shape[0])
+        _check(lib().gr_create(C.byref(self._h), self.n_inst, int(co[0].shape[0]),
+                               *[c.ctypes.data_as(C.c_void_p) for c in co],
+                               ic.ctypes.data_as(C.c_void_p), int(max_entries_per_inst),
+                               int(max_len), int(max_requests)), "gr_create")
+
+    def close(self) -> None:
+        if self._h:
+            h, self._h = self._h, C.c_void_p()
+            _check(lib().gr_destroy(h), "gr_destroy")
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def gr_build_status(self, act_off, act_prompt, act_gen, act_rem, q_off, q_prompt, q_len,
+                        out_act_finish, out_q_finish=None, out_d=None, out_rank=None) -> None:
+        import torch
+        i32, f32 = torch.int32, torch.float32
+        na, nq, M = act_prompt.numel(), q_prompt.numel(), self.n_inst
+        _check(lib().gr_build_status(
+            self._h, _dev(act_off, i32, "act_off", M + 1), _dev(act_prompt, i32, "act_prompt"),
+            _dev(act_gen, i32, "act_gen", na), _dev(act_rem, i32, "act_rem", na), na,
+            _dev(q_off, i32, "q_off", M + 1), _dev(q_prompt, i32, "q_prompt"),
+            _dev(q_len, i32, "q_len", nq), nq,
+            _dev(out_act_finish, f32, "out_act_finish", na), _dev(out_q_finish, f32, "out_q_finish", nq),
+            _dev(out_d, torch.float64, "out_d", M), _dev(out_rank, i32, "out_rank", M),
+            _stream()), "gr_build_status")
+
+    def gr_score_route(self, ctx0, pred_len, budget, out_inst, out_slack, exclude_inst=None,
+                       out_fallback=None, out_T=None) -> None:
+        import torch
+        i32, f32 = torch.int32, torch.float32
+        n = ctx0.numel()
+        _check(lib().gr_score_route(
+            self._h, n, _dev(ctx0, i32, "ctx0"), _dev(pred_len, i32, "pred_len", n),
+            _dev(budget, f32, "budget", n), _dev(exclude_inst, i32, "exclude_inst", n),
+            _dev(out_inst, i32, "out_inst", n), _dev(out_slack, f32, "out_slack", n),
+            _dev(out_fallback, torch.uint8, "out_fallback", n),
+            _dev(out_T, f32, "out_T", n * self.n_inst), _stream()), "gr_score_route")
+
+    def gr_risk_scan(self, act_off, act_prompt, act_gen, act_rem_refreshed, q_off, q_prompt, q_len,
+                     act_budget, out_flag, out_finish, out_target, out_target_slack,
+                     out_n_flagged=None) -> None:
+        import torch
+        i32, f32 = torch.int32, torch.float32
+        na, nq, M = act_prompt.numel(), q_prompt.numel(), self.n_inst
+        _check(lib().gr_risk_scan(
+            self._h, _dev(act_off, i32, "act_off", M + 1), _dev(act_prompt, i32, "act_prompt"),
+            _dev(act_gen, i32, "act_gen", na), _dev(act_rem_refreshed, i32, "act_rem_refreshed", na), na,
+            _dev(q_off, i32, "q_off", M + 1), _dev(q_prompt, i32, "q_prompt"),
+            _dev(q_len, i32, "q_len", nq), nq,
+            _dev(act_budget, f32, "act_budget", na), _dev(out_flag, torch.uint8, "out_flag", na),
+            _dev(out_finish, f32, "out_finish", na), _dev(out_target, i32, "out_target", na),
+            _dev(out_target_slack, f32, "out_target_slack", na),
+            _dev(out_n_flagged, i32, "out_n_flagged", 1), _stream()), "gr_risk_scan")
+
+    def gr_device_status(self) -> int:
+        bits = C.c_int32(0)
+        _check(lib().gr_device_status(self._h, C.byref(bits)), "gr_device_status")
+        return int(bits.value)

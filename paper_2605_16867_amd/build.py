@@ -1,0 +1,32 @@
+"""Build libgoodroute.so for gfx950 with hipcc (in-tree, next to the sources)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(_HERE)
+CSRC = os.path.join(_HERE, "csrc")
+LIB = os.path.join(CSRC, "libgoodroute.so")
+SOURCES = ["goodroute.hip"]
+
+
+def hipcc_command() -> list:
+    return ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+            "-ffp-contract=off",
+            # packed-FP32 instructions stay off: ordinary float code must not be fused into them
+            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-I", os.path.join(ROOT, "include"),
+            "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+
+
+def build_library(verbose: bool = False) -> str:
+    cmd = hipcc_command()
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    build_library(verbose=True)

@@ -1,0 +1,201 @@
+"""GPU-vs-reference comparison shared by the GPU tests, the smoke check and the
+benchmark's self-check.  Runs the three library calls through the binding on
+``cuda:0`` and compares every output with ``oracle/`` on the same inputs.
+
+Bars.  Finish times and pair latencies: relative 1e-4 (fp32 on the GPU, fp64
+reference).  d_g and the capability rank: bit-exact.  Choices and flags: equal
+to the reference wherever the decision does not hinge on a latency lying within
+1e-4 (relative) of the deadline or of a competing latency; those few are
+counted as "ambiguous" and must still be an answer that is right for some
+latency within the band.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+
+import oracle
+from paper_2605_16867_amd import binding
+
+EPS = 1e-4
+
+
+def classify_choices(T, D, rank, exclude, picked):
+    """T: [n, M] fp64 reference latencies; D: [n]; rank: [M]; exclude: [n] or None;
+    picked: [n] instance chosen by the GPU.  Returns (want, robust, admissible):
+    the reference choice, whether it is decided outside the band, and whether the
+    GPU's pick is acceptable."""
+    n, M = T.shape
+    T = T.copy()
+    if exclude is not None:
+        ok = exclude >= 0
+        T[np.flatnonzero(ok), exclude[ok]] = np.inf
+    order = np.argsort(rank, kind="stable")
+    To = T[:, order]                                   # columns in capability order
+    finite = np.isfinite(To)
+    F = (To <= D[:, None]) & finite
+    SF = (To * (1 + EPS) <= D[:, None]) & finite
+    PF = (To * (1 - EPS) <= D[:, None]) & finite
+    first = lambda m: np.where(m.any(axis=1), m.argmax(axis=1), M)
+    f1, s1, p1 = first(F), first(SF), first(PF)
+    Tmin = To.min(axis=1)
+    # fallback: smallest T, ties to the lowest instance index
+    amin = np.argmin(T, axis=1)
+    want = np.where(f1 < M, order[np.minimum(f1, M - 1)], amin).astype(np.int64)
+    none_allowed = ~np.isfinite(Tmin)
+    want[none_allowed] = -1
+
+    srt = np.sort(T, axis=1)
+    second = srt[:, 1] if M > 1 else np.full(n, np.inf)
+    robust_fb = second > Tmin * (1 + 2 * EPS)
+    robust = np.where(p1 < M, p1 == s1, robust_fb) | none_allowed
+
+    pos = np.empty(M, dtype=np.int64)
+    pos[order] = np.arange(M)
+    ppos = np.where(picked >= 0, pos[np.maximum(picked, 0)], M)     # GPU pick in capability order
+    rows = np.arange(n)
+    pT = np.where(picked >= 0, T[rows, np.maximum(picked, 0)], np.inf)
+    in_PF = (picked >= 0) & (pT * (1 - EPS) <= D) & np.isfinite(pT)
+    near_min = (picked >= 0) & (pT <= Tmin * (1 + 2 * EPS))
+    adm = np.where(s1 < M, in_PF & (ppos <= s1),
+                   np.where(p1 < M, in_PF | near_min, near_min))
+    adm = np.where(none_allowed, picked == -1, adm)
+    return want, robust, adm
+
+
+def check_choices(name, T, D, rank, exclude, picked, slack, rep):
+    want, robust, adm = classify_choices(T, D, rank, exclude, picked)
+    bad = robust & (picked != want)
+    assert not bad.any(), f"{name}: {bad.sum()} robust choices differ, first at {np.flatnonzero(bad)[:5]}"
+    assert adm[~robust].all(), f"{name}: {(~adm[~robust]).sum()} ambiguous choices not admissible"
+    ok = picked >= 0
+    rows = np.flatnonzero(ok)
+    Tp = T[rows, picked[ok]]
+    err = np.abs(slack[ok].astype(np.float64) - (D[ok] - Tp))
+    tol = EPS * np.maximum(Tp, np.abs(D[ok])) + 1e-30
+    assert np.all(err <= tol), f"{name}: slack off by up to {np.max(err / tol):.3g} x tolerance"
+    rep[name + "_ambiguous"] = int((~robust).sum())
+    rep[name + "_n"] = int(len(picked))
+    rep[name + "_feasible_frac"] = float(np.mean((T <= D[:, None]).any(axis=1))) if len(D) else 0.0
+    return want
+
+
+def rel_err(got, want):
+    want = np.asarray(want, dtype=np.float64)
+    return np.abs(np.asarray(got, dtype=np.float64) - want) / np.maximum(np.abs(want), 1e-300)
+
+
+def upload(fl, device="cuda:0"):
+    import torch
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+    return {k: t(getattr(fl, k)) for k in
+            ("act_off", "act_prompt", "act_gen", "act_rem", "act_rem_refreshed", "act_budget",
+             "q_off", "q_prompt", "q_len", "in_prompt", "in_len", "in_budget")}
+
+
+def make_handle(fl, max_requests: Optional[int] = None):
+    me = int(max(np.diff(fl.act_off) + np.diff(fl.q_off))) if fl.n_inst else 0
+    return binding.Fleet(fl.coef["delta"], fl.coef["alpha"], fl.coef["beta"], fl.coef["gamma"],
+                         fl.inst_class, max(me, 1), fl.spec.max_len,
+                         max(len(fl.in_prompt), 1) if max_requests is None else max_requests)
+
+
+def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit: int = 1 << 25,
+                  exclude=None):
+    """Run the whole path on the GPU and check it.  ``sample``: number of
+    requests (and of active requests) checked against the reference; None = all."""
+    import torch
+    dev = "cuda:0"
+    rep = {}
+    d = upload(fl, dev)
+    M = fl.n_inst
+    na, nq, R = len(fl.act_prompt), len(fl.q_prompt), len(fl.in_prompt)
+    h = make_handle(fl)
+    rng = np.random.default_rng(seed)
+
+    # ---- step 1: status
+    fin = torch.full((na,), float("nan"), dtype=torch.float32, device=dev)
+    qfin = torch.full((nq,), float("nan"), dtype=torch.float32, device=dev)
+    dd = torch.zeros(M, dtype=torch.float64, device=dev)
+    rk = torch.zeros(M, dtype=torch.int32, device=dev)
+    h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"],
+                      d["q_off"], d["q_prompt"], d["q_len"], fin, qfin, dd, rk)
+    torch.cuda.synchronize()
+    sim = oracle.simulate(fl)
+    e = rel_err(fin.cpu().numpy(), sim.act_finish)
+    assert na == 0 or e.max() <= EPS, f"active finish rel err {e.max():.3g}"
+    rep["finish_rel_err"] = float(e.max()) if na else 0.0
+    if nq:
+        e = rel_err(qfin.cpu().numpy(), sim.q_finish)
+        assert e.max() <= EPS, f"queued finish rel err {e.max():.3g}"
+    assert np.array_equal(dd.cpu().numpy(), sim.d), "d_g not bit-exact"
+    assert np.array_equal(rk.cpu().numpy(), sim.rank), "capability rank differs"
+
+    # ---- step 2: route
+    if R:
+        ex_np = None if exclude is None else np.ascontiguousarray(exclude, dtype=np.int32)
+        inst = torch.full((R,), -7, dtype=torch.int32, device=dev)
+        slack = torch.zeros(R, dtype=torch.float32, device=dev)
+        fb = torch.zeros(R, dtype=torch.uint8, device=dev)
+        want_T = R * M <= full_T_limit
+        outT = torch.zeros(R * M, dtype=torch.float32, device=dev) if want_T else None
+        h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, slack,
+                         exclude_inst=None if ex_np is None else torch.from_numpy(ex_np).to(dev),
+                         out_fallback=fb, out_T=outT)
+        torch.cuda.synchronize()
+        idx = np.arange(R) if sample is None or sample >= R else np.sort(rng.choice(R, sample, replace=False))
+        T = sim.pair_T(fl.in_prompt[idx], fl.in_len[idx])
+        D = fl.in_budget[idx].astype(np.float64)
+        if want_T:
+            e = rel_err(outT.cpu().numpy().reshape(R, M)[idx], T)
+            assert e.max() <= EPS, f"pair latency rel err {e.max():.3g}"
+            rep["pair_T_rel_err"] = float(e.max())
+        picked = inst.cpu().numpy()[idx].astype(np.int64)
+        want = check_choices("route", T, D, sim.rank, None if ex_np is None else ex_np[idx], picked,
+                             slack.cpu().numpy()[idx], rep)
+        ref = sim.route(fl.in_prompt[idx], fl.in_len[idx], D,
+                        exclude=None if ex_np is None else ex_np[idx])
+        assert np.array_equal(ref.inst, want), "reference scan and classifier disagree"
+        fbn = fb.cpu().numpy()[idx]
+        same = picked == want
+        assert np.array_equal(fbn[same], ref.fallback[same]), "fallback bit differs on equal choices"
+
+    # ---- step 3: risk scan
+    if na:
+        flag = torch.full((na,), 9, dtype=torch.uint8, device=dev)
+        fin2 = torch.full((na,), float("nan"), dtype=torch.float32, device=dev)
+        tgt = torch.full((na,), -7, dtype=torch.int32, device=dev)
+        tsl = torch.full((na,), float("nan"), dtype=torch.float32, device=dev)
+        nfl = torch.zeros(1, dtype=torch.int32, device=dev)
+        h.gr_risk_scan(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem_refreshed"],
+                       d["q_off"], d["q_prompt"], d["q_len"], d["act_budget"],
+                       flag, fin2, tgt, tsl, nfl)
+        torch.cuda.synchronize()
+        idx = np.arange(na) if sample is None or sample >= na else np.sort(rng.choice(na, sample, replace=False))
+        rs = oracle.risk_scan(fl, fl.act_rem_refreshed, fl.act_budget, only=idx)
+        e = rel_err(fin2.cpu().numpy(), rs.finish)
+        assert e.max() <= EPS, f"risk-scan finish rel err {e.max():.3g}"
+        budget = fl.act_budget.astype(np.float64)
+        band = np.abs(rs.finish - budget) <= EPS * np.maximum(rs.finish, np.abs(budget))
+        gflag = flag.cpu().numpy()
+        assert set(np.unique(gflag)) <= {0, 1}
+        bad = (gflag != rs.flag) & ~band
+        assert not bad.any(), f"{bad.sum()} robust risk flags differ"
+        rep["flag_ambiguous"] = int(band.sum())
+        rep["flag_frac"] = float(gflag.mean())
+        assert int(nfl.item()) == int(gflag.sum()), "flag count differs from flags"
+        gt, gs = tgt.cpu().numpy(), tsl.cpu().numpy()
+        assert np.all(gt[gflag == 0] == -1) and np.all(gs[gflag == 0] == 0.0)
+        both = idx[(gflag[idx] == 1) & (rs.flag[idx] == 1)]
+        if len(both):
+            inst_of = (np.searchsorted(fl.act_off, both, side="right") - 1).astype(np.int32)
+            c0 = fl.act_prompt[both].astype(np.int64) + fl.act_gen[both]
+            T = rs.sim.pair_T(c0, fl.act_rem_refreshed[both])
+            want = check_choices("migrate", T, budget[both], rs.sim.rank, inst_of,
+                                 gt[both].astype(np.int64), gs[both], rep)
+            assert np.array_equal(want, rs.target[both]), "reference scan and classifier disagree"
+            assert np.all(gt[both] != inst_of) or M == 1
+    assert h.gr_device_status() == 0, "device status bits raised on in-contract input"
+    h.close()
+    return rep

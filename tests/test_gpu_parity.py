@@ -1,0 +1,48 @@
+"""GPU parity: the three library calls, through the C interface, against the
+CPU reference on the same seeded inputs (bars in tests/parity.py)."""
+import numpy as np
+import pytest
+
+from paper_2605_16867_amd import workloads
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def report(name, rep):
+    print(f"\n[{name}] " + " ".join(f"{k}={v}" for k, v in rep.items()), flush=True)
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid"])
+def test_small_fleets_every_output(name):
+    rep = parity.run_and_check(workloads.make_fleet(workloads.spec(name)))
+    report(name, rep)
+
+
+@pytest.mark.parametrize("scale", [2.0, 4.0, 16.0, 64.0])
+def test_mid_fleet_decision_mix(scale):
+    """Same shapes, looser SLOs, uneven occupancy, one idle instance: exercises
+    the just-enough branch next to the fallback."""
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=scale, occupancy_jitter=True,
+                                             seed=int(scale)))
+    rep = parity.run_and_check(fl)
+    report(f"mid x{scale}", rep)
+    if scale <= 4.0:
+        assert 0.02 < rep["route_feasible_frac"] < 1.0
+
+
+def test_route_with_exclusions():
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=3.0, seed=5))
+    rng = np.random.default_rng(1)
+    ex = rng.integers(-1, fl.n_inst, len(fl.in_prompt)).astype(np.int32)
+    report("exclude", parity.run_and_check(fl, exclude=ex))
+
+
+def test_large_fleet_sampled():
+    fl = workloads.make_fleet(workloads.spec("large"))
+    report("large", parity.run_and_check(fl, sample=4096, full_T_limit=1 << 25))
+
+
+def test_large_fleet_loose_slo_sampled():
+    fl = workloads.make_fleet(workloads.spec("large", slo_scale=4.0, occupancy_jitter=True, seed=2))
+    report("large x4", parity.run_and_check(fl, sample=4096))
