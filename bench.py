@@ -1,0 +1,209 @@
+#!/usr/bin/env python3
+"""Benchmark of the routing path on one MI355X.
+
+One step = one pass of the whole path over one synthetic fleet, inputs already
+in HBM: gr_build_status, gr_score_route over the incoming batch, gr_risk_scan
+(status rebuilt from the refreshed lengths, flags, migration targets).
+
+Prints ONE JSON line.  ``value`` is pair-estimates per second over the timed
+steps: (incoming x instances) + (flagged x (instances - 1)) + one finish
+estimate per held request in each of the two status builds, divided by wall
+time.  ``roofline`` describes the kernel that took the most time, timed with
+HIP events around each of its launches inside the timed region;
+``cpu_baseline`` is the CPU reference timed on this machine's host cores on a
+bounded sample of the same fleet.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CU x 128 lanes x 2 flop x 2.4 GHz (packed FMA)
+
+# Algorithmic work per unit, independent of how the kernels are organised.
+# Scoring, per (request, instance) pair: Eq. 2 from per-(instance, length) terms
+# (one multiply-add = 2 flops), the feasibility compare of Alg. 1 (1), and the two
+# running selections, best capability among feasible and least latency (compare +
+# select each = 4): 7 operations, counted as flops.
+OPS_PER_PAIR = 7.0
+# Status build, per held request: read prompt, generated, remaining (12 B), write
+# finish (4 B) and one table entry (12 B); the risk scan also reads the budget (4 B)
+# and writes the flag (1 B).
+BUILD_BYTES_PER_ENTRY = 28.0
+SCAN_EXTRA_BYTES_PER_ENTRY = 5.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="heavy", help="tiny | mid | large | migrate | heavy")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0,
+                    help="target CPU time of the reference sample (0: skip)")
+    return ap.parse_args()
+
+
+def cpu_baseline(fl, pairs_route, pairs_migrate, entries, n_flagged, target_s):
+    """Time the CPU reference (as it stands) on a bounded sample of this fleet and
+    scale the two scanning legs to the whole step."""
+    import oracle
+    M = fl.n_inst
+    rng = np.random.default_rng(0)
+    t0 = time.perf_counter()
+    sim = oracle.simulate(fl)
+    t_sim = time.perf_counter() - t0
+    R, na = len(fl.in_prompt), len(fl.act_prompt)
+    budget = max(target_s - 2 * t_sim, 2.0) / 2
+
+    def timed_route(n):
+        idx = rng.choice(R, min(n, R), replace=False)
+        t = time.perf_counter()
+        sim.route(fl.in_prompt[idx], fl.in_len[idx], fl.in_budget[idx].astype(np.float64))
+        return time.perf_counter() - t, len(idx)
+
+    t_route = n_route = 0
+    if R:
+        t_probe, n_probe = timed_route(512)
+        t_route, n_route = timed_route(int(max(512, n_probe * budget / max(t_probe, 1e-6))))
+    t1 = time.perf_counter()
+    sim2 = oracle.simulate(fl, fl.act_rem_refreshed)
+    flag = np.flatnonzero(sim2.act_finish > fl.act_budget.astype(np.float64))
+    t_sim2 = time.perf_counter() - t1
+    t_mig = n_mig = 0
+    if len(flag):
+        def timed_mig(n):
+            idx = rng.choice(flag, min(n, len(flag)), replace=False)
+            inst_of = (np.searchsorted(fl.act_off, idx, side="right") - 1).astype(np.int32)
+            c0 = fl.act_prompt[idx].astype(np.int64) + fl.act_gen[idx]
+            t = time.perf_counter()
+            sim2.route(c0, fl.act_rem_refreshed[idx], fl.act_budget[idx].astype(np.float64),
+                       exclude=inst_of)
+            return time.perf_counter() - t, len(idx)
+        t_probe, n_probe = timed_mig(512)
+        t_mig, n_mig = timed_mig(int(max(512, n_probe * budget / max(t_probe, 1e-6))))
+    est = t_sim + t_sim2
+    if n_route:
+        est += t_route * R / n_route
+    if n_mig:
+        est += t_mig * len(flag) / n_mig
+    total_pairs = pairs_route + len(flag) * (M - 1) + 2 * entries
+    return {
+        "value": total_pairs / est, "unit": "pairs/s", "cores": oracle.threads(), "kind": "oracle",
+        "sample": (f"both step-by-step simulations of all {M} instances ({t_sim + t_sim2:.2f} s), "
+                   f"exhaustive scan of {n_route} of {R} incoming requests ({t_route:.2f} s) and of "
+                   f"{n_mig} of {len(flag)} flagged requests ({t_mig:.2f} s), scan times scaled to the "
+                   f"full batch; estimated CPU step {est:.1f} s"),
+    }
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this path runs on one GPU; --gpus must be 1 "
+              "(no collectives or sharding are part of this build)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2605_16867_amd import workloads
+    from tests import parity
+
+    fl = workloads.make_fleet(workloads.spec(a.config))
+    M, R = fl.n_inst, len(fl.in_prompt)
+    na, nq = len(fl.act_prompt), len(fl.q_prompt)
+    entries = na + nq
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    d = parity.upload(fl, dev)
+    h = parity.make_handle(fl)
+
+    fin = torch.empty(na, dtype=torch.float32, device=dev)
+    inst = torch.empty(max(R, 1), dtype=torch.int32, device=dev)
+    slack = torch.empty(max(R, 1), dtype=torch.float32, device=dev)
+    flag = torch.empty(na, dtype=torch.uint8, device=dev)
+    fin2 = torch.empty(na, dtype=torch.float32, device=dev)
+    tgt = torch.empty(na, dtype=torch.int32, device=dev)
+    tsl = torch.empty(na, dtype=torch.float32, device=dev)
+    nfl = torch.zeros(1, dtype=torch.int32, device=dev)
+
+    def step():
+        h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"],
+                          d["q_off"], d["q_prompt"], d["q_len"], fin)
+        if R:
+            h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, slack)
+        h.gr_risk_scan(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem_refreshed"],
+                       d["q_off"], d["q_prompt"], d["q_len"], d["act_budget"],
+                       flag, fin2, tgt, tsl, nfl)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    h.gr_profile_enable(16 * a.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = h.gr_profile_read()
+    h.gr_profile_enable(0)
+
+    n_flagged = int(nfl.item())
+    pairs_route, pairs_mig = R * M, n_flagged * (M - 1)
+    pairs_step = pairs_route + pairs_mig + 2 * entries
+    ms_step = dt / a.steps * 1e3
+
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        if not cnt:
+            continue
+        avg_ms = ms / cnt
+        k = {"avg_ms": avg_ms, "launches_per_step": cnt / a.steps}
+        if name.startswith("k_score"):
+            pairs = pairs_route if "route" in name else pairs_mig
+            k.update(bound="alu", pairs=pairs, pairs_per_s=pairs / (avg_ms * 1e-3),
+                     achieved=pairs * OPS_PER_PAIR / (avg_ms * 1e-3) / 1e12,
+                     peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s")
+        elif name == "k_build":
+            # two launches per step: plain build, and the scan's rebuild with budget + flag
+            by = entries * (BUILD_BYTES_PER_ENTRY + SCAN_EXTRA_BYTES_PER_ENTRY / 2)
+            k.update(bound="hbm", achieved=by / (avg_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
+        else:
+            continue
+        k["frac"] = k["achieved"] / k["peak"]
+        kernels[name] = k
+    dominant = max(kernels, key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
+    dk = kernels[dominant]
+    roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
+                "unit": dk["unit"], "frac": dk["frac"], "traffic": None,
+                "avg_launch_ms": dk["avg_ms"]}
+
+    out = {
+        "metric": "request x instance finish-estimates per second",
+        "value": pairs_step / (dt / a.steps), "unit": "pairs/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": a.config, "instances": M, "held_requests": entries,
+                   "incoming": R, "flagged": n_flagged, "route_pairs": pairs_route,
+                   "migration_pairs": pairs_mig},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if a.cpu_seconds > 0:
+        out["cpu_baseline"] = cpu_baseline(fl, pairs_route, pairs_mig, entries, n_flagged, a.cpu_seconds)
+    h.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -175,6 +175,21 @@ int gr_risk_scan(gr_fleet* f,
  */
 int gr_device_status(gr_fleet* f, int32_t* out_bits);
 
+/*
+ * Per-kernel timing, for benchmarks (not cited from the paper: a measuring aid).
+ * gr_profile_enable(f, n) with n > 0 makes every kernel launch of the following
+ * calls record a pair of HIP events on the call's stream, up to n launches
+ * (events are created here, not in the calls); n = 0 switches timing off.
+ * gr_profile_read synchronises the device, adds up the elapsed time and the
+ * number of launches per kernel id since the last read into HOST arrays of
+ * n_kernels entries, and forgets them.  Kernel ids run from 0 to
+ * gr_profile_kernel_count() - 1; gr_profile_kernel_name gives a static name.
+ */
+int gr_profile_enable(gr_fleet* f, int32_t max_launches);
+int gr_profile_read(gr_fleet* f, int32_t n_kernels, double* total_ms, int64_t* launches);
+int32_t gr_profile_kernel_count(void);
+const char* gr_profile_kernel_name(int32_t id);
+
 /* Static, human-readable text for a return code. */
 const char* gr_strerror(int code);
 

@@ -13,7 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libgoodroute.so")
 
 EXPORTS = ("gr_create", "gr_destroy", "gr_build_status", "gr_score_route", "gr_risk_scan",
-           "gr_device_status", "gr_strerror")
+           "gr_device_status", "gr_strerror", "gr_profile_enable", "gr_profile_read",
+           "gr_profile_kernel_count", "gr_profile_kernel_name")
 
 _lib = None
 
@@ -44,6 +45,14 @@ def lib() -> C.CDLL:
         l.gr_risk_scan.argtypes = [p, p, p, p, p, i64, p, p, p, i64, p, p, p, p, p, p, p]
         l.gr_device_status.restype = C.c_int
         l.gr_device_status.argtypes = [p, C.POINTER(i32)]
+        l.gr_profile_enable.restype = C.c_int
+        l.gr_profile_enable.argtypes = [p, i32]
+        l.gr_profile_read.restype = C.c_int
+        l.gr_profile_read.argtypes = [p, i32, p, p]
+        l.gr_profile_kernel_count.restype = i32
+        l.gr_profile_kernel_count.argtypes = []
+        l.gr_profile_kernel_name.restype = C.c_char_p
+        l.gr_profile_kernel_name.argtypes = [i32]
         l.gr_strerror.restype = C.c_char_p
         l.gr_strerror.argtypes = [C.c_int]
         _lib = l
@@ -142,6 +151,17 @@ class Fleet:
             _dev(out_finish, f32, "out_finish", na), _dev(out_target, i32, "out_target", na),
             _dev(out_target_slack, f32, "out_target_slack", na),
             _dev(out_n_flagged, i32, "out_n_flagged", 1), _stream()), "gr_risk_scan")
+
+    def gr_profile_enable(self, max_launches: int) -> None:
+        _check(lib().gr_profile_enable(self._h, int(max_launches)), "gr_profile_enable")
+
+    def gr_profile_read(self) -> dict:
+        """{kernel name: (total milliseconds, launches)} since the last read."""
+        n = int(lib().gr_profile_kernel_count())
+        ms = (C.c_double * n)()
+        cnt = (C.c_int64 * n)()
+        _check(lib().gr_profile_read(self._h, n, ms, cnt), "gr_profile_read")
+        return {lib().gr_profile_kernel_name(k).decode(): (float(ms[k]), int(cnt[k])) for k in range(n)}
 
     def gr_device_status(self) -> int:
         bits = C.c_int32(0)

@@ -19,6 +19,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <new>
+#include <vector>
 
 #include "goodroute.h"
 
@@ -36,7 +37,19 @@ struct ClassCoef {
 
 }  // namespace
 
+// Kernel ids for the optional per-kernel timing (gr_profile_*).
+enum KernelId { kBuild = 0, kRank, kScoreRoute, kCompact, kScoreMigrate, kNumKernels };
+static const char* const kKernelNames[kNumKernels] = {"k_build", "k_rank", "k_score<route>", "k_compact",
+                                                      "k_score<migrate>"};
+
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> events;  // pairs: start, stop
+    std::vector<int> ids;            // kernel id of each recorded pair
+};
+
 struct gr_fleet {
+    Profiler prof;
     int n_inst = 0, n_class = 0, max_entries = 0, max_len = 0;
     int64_t max_requests = 0;
     int64_t max_active = 0;
@@ -422,6 +435,24 @@ __global__ __launch_bounds__(kBlock) void k_compact(const uint8_t* flag, int64_t
 __global__ void k_copy_count(const int* counter, int* out) { *out = *counter; }
 
 // ------------------------------------------------------------------ host side
+// Brackets one kernel launch with a pair of events when timing is switched on.
+struct ProfScope {
+    Profiler& p;
+    hipStream_t s;
+    size_t slot = SIZE_MAX;
+    ProfScope(gr_fleet* f, int id, hipStream_t stream) : p(f->prof), s(stream)
+    {
+        if (!p.on || (p.ids.size() + 1) * 2 > p.events.size()) return;
+        slot = p.ids.size();
+        p.ids.push_back(id);
+        (void)hipEventRecord(p.events[2 * slot], s);
+    }
+    ~ProfScope()
+    {
+        if (slot != SIZE_MAX) (void)hipEventRecord(p.events[2 * slot + 1], s);
+    }
+};
+
 int bits_for(int64_t v)
 {
     int b = 0;
@@ -453,9 +484,15 @@ int launch_build(gr_fleet* f, const int32_t* act_off, const int32_t* act_prompt,
     b.hN = f->hN; b.hQ = f->hQ; b.hD = f->hD; b.act_inst = f->act_inst; b.counters = f->counters;
     b.max_entries = f->max_entries; b.ncap = f->ncap; b.tstride = f->tstride;
     b.idx_bits = f->idx_bits; b.key_bits = f->key_bits; b.max_len = f->max_len;
-    hipLaunchKernelGGL(k_build, dim3(f->n_inst), dim3(kBlock), build_lds_bytes(f), s, b);
-    hipLaunchKernelGGL(k_rank, dim3((f->n_inst + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
-                       f->hD, f->n_inst, f->rank, f->order, out_rank);
+    {
+        ProfScope ps(f, kBuild, s);
+        hipLaunchKernelGGL(k_build, dim3(f->n_inst), dim3(kBlock), build_lds_bytes(f), s, b);
+    }
+    {
+        ProfScope ps(f, kRank, s);
+        hipLaunchKernelGGL(k_rank, dim3((f->n_inst + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
+                           f->hD, f->n_inst, f->rank, f->order, out_rank);
+    }
     if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
     f->has_status = true;
     return GR_OK;
@@ -551,6 +588,7 @@ int gr_destroy(gr_fleet* f)
     int rc = GR_OK;
     for (void* p : ptrs)
         if (p && hipFree(p) != hipSuccess) rc = GR_ERR_HIP;
+    for (hipEvent_t e : f->prof.events) (void)hipEventDestroy(e);
     delete f;
     return rc;
 }
@@ -584,8 +622,11 @@ int gr_score_route(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_
     a.n_req = n_req;
     a.out_inst = out_inst; a.out_slack = out_slack; a.out_fallback = out_fallback; a.out_T = out_T;
     fill_score_tables(f, a);
-    hipLaunchKernelGGL(k_score<false>, dim3((unsigned)((n_req + kBlock - 1) / kBlock)), dim3(kBlock),
-                       (size_t)f->tstride * 12, static_cast<hipStream_t>(hip_stream), a);
+    {
+        ProfScope ps(f, kScoreRoute, static_cast<hipStream_t>(hip_stream));
+        hipLaunchKernelGGL(k_score<false>, dim3((unsigned)((n_req + kBlock - 1) / kBlock)), dim3(kBlock),
+                           (size_t)f->tstride * 12, static_cast<hipStream_t>(hip_stream), a);
+    }
     return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
 }
 
@@ -608,13 +649,17 @@ int gr_risk_scan(gr_fleet* f, const int32_t* act_off, const int32_t* act_prompt,
     if (rc != GR_OK) return rc;
     if (n_active > 0) {
         const unsigned blocks = (unsigned)((n_active + kBlock - 1) / kBlock);
-        hipLaunchKernelGGL(k_compact, dim3(blocks), dim3(kBlock), 0, s, out_flag, n_active, f->sel,
-                           f->counters, out_target, out_target_slack);
+        {
+            ProfScope ps(f, kCompact, s);
+            hipLaunchKernelGGL(k_compact, dim3(blocks), dim3(kBlock), 0, s, out_flag, n_active, f->sel,
+                               f->counters, out_target, out_target_slack);
+        }
         ScoreArgs a{};
         a.act_prompt = act_prompt; a.act_gen = act_gen; a.act_rem = act_rem_refreshed;
         a.act_inst = f->act_inst; a.sel = f->sel; a.n_sel = f->counters; a.act_budget = act_budget;
         a.out_inst = out_target; a.out_slack = out_target_slack;
         fill_score_tables(f, a);
+        ProfScope ps(f, kScoreMigrate, s);
         hipLaunchKernelGGL(k_score<true>, dim3(blocks), dim3(kBlock), (size_t)f->tstride * 12, s, a);
     }
     if (out_n_flagged) hipLaunchKernelGGL(k_copy_count, dim3(1), dim3(1), 0, s, f->counters, out_n_flagged);
@@ -629,6 +674,44 @@ int gr_device_status(gr_fleet* f, int32_t* out_bits)
     if (hipMemcpy(&v, f->counters + 1, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return GR_ERR_HIP;
     *out_bits = v;
     return GR_OK;
+}
+
+int gr_profile_enable(gr_fleet* f, int32_t max_launches)
+{
+    if (!f || max_launches < 0) return GR_ERR_INVALID_ARG;
+    Profiler& p = f->prof;
+    if (hipDeviceSynchronize() != hipSuccess) return GR_ERR_HIP;
+    p.ids.clear();
+    p.on = max_launches > 0;
+    p.ids.reserve((size_t)max_launches);
+    while (p.events.size() < (size_t)max_launches * 2) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { p.on = false; return GR_ERR_HIP; }
+        p.events.push_back(e);
+    }
+    return GR_OK;
+}
+
+int gr_profile_read(gr_fleet* f, int32_t n_kernels, double* total_ms, int64_t* launches)
+{
+    if (!f || n_kernels < 0 || (n_kernels > 0 && (!total_ms || !launches))) return GR_ERR_INVALID_ARG;
+    if (hipDeviceSynchronize() != hipSuccess) return GR_ERR_HIP;
+    Profiler& p = f->prof;
+    for (int k = 0; k < n_kernels; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
+    for (size_t i = 0; i < p.ids.size(); ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.events[2 * i], p.events[2 * i + 1]) != hipSuccess) return GR_ERR_HIP;
+        if (p.ids[i] < n_kernels) { total_ms[p.ids[i]] += ms; launches[p.ids[i]] += 1; }
+    }
+    p.ids.clear();
+    return GR_OK;
+}
+
+int32_t gr_profile_kernel_count(void) { return kNumKernels; }
+
+const char* gr_profile_kernel_name(int32_t id)
+{
+    return id >= 0 && id < kNumKernels ? kKernelNames[id] : "";
 }
 
 const char* gr_strerror(int code)
