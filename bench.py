@@ -147,7 +147,7 @@ def main():
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
-    h.gr_profile_enable(16 * a.steps)
+    h.gr_profile_enable(32 * a.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(a.steps):
@@ -168,7 +168,7 @@ def main():
             continue
         avg_ms = ms / cnt
         k = {"avg_ms": avg_ms, "launches_per_step": cnt / a.steps}
-        if name.startswith("k_score"):
+        if name.startswith("k_tile"):
             pairs = pairs_route if "route" in name else pairs_mig
             k.update(bound="alu", pairs=pairs, pairs_per_s=pairs / (avg_ms * 1e-3),
                      achieved=pairs * OPS_PER_PAIR / (avg_ms * 1e-3) / 1e12,

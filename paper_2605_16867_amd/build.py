@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(CSRC, "libgoodroute.so")
-SOURCES = ["goodroute.hip"]
+SOURCES = ["api.hip", "status.hip", "score.hip"]
 
 
 def hipcc_command() -> list:

@@ -1,0 +1,267 @@
+// Host entry points of libgoodroute: the fleet handle, argument checks and the
+// order in which the kernels of status.hip and score.hip are queued.
+#include <cstdlib>
+#include <new>
+
+#include "common.h"
+
+namespace gr {
+namespace {
+
+const char* const kKernelNames[kNumKernels] = {
+    "k_build", "k_rank_count", "k_rank_final",
+    "k_hist<route>", "k_scan<route>", "k_scatter<route>", "k_memo<route>", "k_tile<route>",
+    "k_hist<migrate>", "k_scan<migrate>", "k_scatter<migrate>", "k_memo<migrate>", "k_tile<migrate>"};
+
+int bits_for(int64_t v)
+{
+    int b = 0;
+    while ((int64_t(1) << b) <= v) ++b;
+    return b;
+}
+
+template <typename T>
+bool dev_alloc(T** p, size_t n)
+{
+    return hipMalloc(reinterpret_cast<void**>(p), (n ? n : 1) * sizeof(T)) == hipSuccess;
+}
+
+bool status_args_ok(const gr_fleet* f, const int32_t* act_off, const int32_t* act_prompt,
+                    const int32_t* act_gen, const int32_t* act_rem, int64_t n_active,
+                    const int32_t* q_off, const int32_t* q_prompt, const int32_t* q_len, int64_t n_queued,
+                    int* rc)
+{
+    *rc = GR_ERR_INVALID_ARG;
+    if (!f || !act_off || !q_off || n_active < 0 || n_queued < 0) return false;
+    if (n_active > 0 && (!act_prompt || !act_gen || !act_rem)) return false;
+    if (n_queued > 0 && (!q_prompt || !q_len)) return false;
+    *rc = GR_ERR_TOO_LARGE;
+    if (n_active > f->max_active || n_queued > f->max_active) return false;
+    *rc = GR_OK;
+    return true;
+}
+
+}  // namespace
+}  // namespace gr
+
+using namespace gr;
+
+extern "C" {
+
+int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
+              const double* delta, const double* alpha, const double* beta, const double* gamma,
+              const int32_t* inst_class, int32_t max_entries_per_inst, int32_t max_len,
+              int64_t max_requests)
+{
+    if (!out) return GR_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (n_inst <= 0 || n_class <= 0 || !delta || !alpha || !beta || !gamma || !inst_class ||
+        max_entries_per_inst < 0 || max_len < 1 || max_requests < 0)
+        return GR_ERR_INVALID_ARG;
+    if (n_class > kMaxClasses || max_entries_per_inst > kMaxEntries || max_len > kMaxLen ||
+        max_requests > (int64_t(1) << 30) || n_inst > (1 << 20))
+        return GR_ERR_TOO_LARGE;
+    for (int c = 0; c < n_class; ++c)
+        if (!(delta[c] >= 0) || !(alpha[c] >= 0) || !(beta[c] >= 0) || !(gamma[c] >= 0))
+            return GR_ERR_INVALID_ARG;
+    for (int g = 0; g < n_inst; ++g)
+        if (inst_class[g] < 0 || inst_class[g] >= n_class) return GR_ERR_INVALID_ARG;
+    const int idx_bits = bits_for(max_entries_per_inst > 0 ? max_entries_per_inst - 1 : 0);
+    const int key_bits = bits_for(max_len);
+    if (idx_bits + key_bits > 32) return GR_ERR_TOO_LARGE;
+    if ((int64_t)n_inst * max_entries_per_inst > (int64_t(1) << 30)) return GR_ERR_TOO_LARGE;
+
+    gr_fleet* f = new (std::nothrow) gr_fleet;
+    if (!f) return GR_ERR_NOMEM;
+    f->n_inst = n_inst; f->n_class = n_class;
+    f->max_entries = max_entries_per_inst; f->max_len = max_len; f->max_requests = max_requests;
+    f->max_active = (int64_t)n_inst * max_entries_per_inst;
+    f->req_cap = f->max_active > max_requests ? f->max_active : max_requests;
+    f->idx_bits = idx_bits > 0 ? idx_bits : 1; f->key_bits = key_bits;
+    f->ncap = ((max_entries_per_inst + kWave - 1) / kWave) * kWave;
+    if (f->ncap == 0) f->ncap = kWave;
+    f->tstride = max_entries_per_inst + 1;
+    f->m_pad = ((n_inst + kWave - 1) / kWave) * kWave;
+    f->bins = max_len + 1;
+    f->row_cap = f->req_cap < f->bins ? f->req_cap : f->bins;
+    if (f->row_cap < 1) f->row_cap = 1;
+    if (hipGetDevice(&f->device) != hipSuccess) { delete f; return GR_ERR_HIP; }
+    if (status_lds_bytes(f) > 160 * 1024 || score_lds_bytes(f) > 160 * 1024) { delete f; return GR_ERR_TOO_LARGE; }
+
+    const size_t tab = (size_t)n_inst * f->tstride;
+    const bool ok =
+        dev_alloc(&f->cls, n_class) && dev_alloc(&f->inst_class, n_inst) &&
+        dev_alloc(&f->tabR, tab) && dev_alloc(&f->tabG, tab) && dev_alloc(&f->tabS, tab) &&
+        dev_alloc(&f->hN, n_inst) && dev_alloc(&f->hQ, n_inst) && dev_alloc(&f->hD, n_inst) &&
+        dev_alloc(&f->rank_acc, n_inst) && dev_alloc(&f->rank, n_inst) && dev_alloc(&f->order, f->m_pad) &&
+        dev_alloc(&f->act_inst, f->max_active) && dev_alloc(&f->counters, 1) &&
+        dev_alloc(&f->len_cnt, f->bins) && dev_alloc(&f->len_base, f->bins) &&
+        dev_alloc(&f->row_len, f->row_cap) && dev_alloc(&f->row_off, f->row_cap + 1) &&
+        dev_alloc(&f->tile_off, f->row_cap + 1) && dev_alloc(&f->totals, 4) &&
+        dev_alloc(&f->recs, f->req_cap) && dev_alloc(&f->memo, (size_t)f->row_cap * f->m_pad);
+    if (!ok) { gr_destroy(f); return GR_ERR_NOMEM; }
+
+    ClassCoef* host = static_cast<ClassCoef*>(malloc(sizeof(ClassCoef) * n_class));
+    if (!host) { gr_destroy(f); return GR_ERR_NOMEM; }
+    for (int c = 0; c < n_class; ++c) host[c] = ClassCoef{delta[c], alpha[c], beta[c], gamma[c]};
+    const hipError_t e1 = hipMemcpy(f->cls, host, sizeof(ClassCoef) * n_class, hipMemcpyHostToDevice);
+    const hipError_t e2 = hipMemcpy(f->inst_class, inst_class, sizeof(int) * n_inst, hipMemcpyHostToDevice);
+    const hipError_t e3 = hipMemset(f->counters, 0, sizeof(int));
+    const hipError_t e4 = hipMemset(f->len_cnt, 0, sizeof(int) * f->bins);
+    const hipError_t e5 = hipMemset(f->totals, 0, sizeof(int) * 4);
+    free(host);
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess) {
+        gr_destroy(f);
+        return GR_ERR_HIP;
+    }
+    if (status_prepare(f) != GR_OK || score_prepare(f) != GR_OK) { gr_destroy(f); return GR_ERR_HIP; }
+    *out = f;
+    return GR_OK;
+}
+
+int gr_destroy(gr_fleet* f)
+{
+    if (!f) return GR_OK;
+    (void)hipDeviceSynchronize();
+    void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabG, f->tabS, f->hN, f->hQ, f->hD, f->rank_acc,
+                    f->rank, f->order, f->act_inst, f->counters, f->len_cnt, f->len_base, f->row_len,
+                    f->row_off, f->tile_off, f->totals, f->recs, f->memo};
+    int rc = GR_OK;
+    for (void* p : ptrs)
+        if (p && hipFree(p) != hipSuccess) rc = GR_ERR_HIP;
+    for (hipEvent_t e : f->prof.events) (void)hipEventDestroy(e);
+    delete f;
+    return rc;
+}
+
+int gr_build_status(gr_fleet* f, const int32_t* act_off, const int32_t* act_prompt,
+                    const int32_t* act_gen, const int32_t* act_rem, int64_t n_active,
+                    const int32_t* q_off, const int32_t* q_prompt, const int32_t* q_len,
+                    int64_t n_queued, float* out_act_finish, float* out_q_finish,
+                    double* out_d, int32_t* out_rank, void* hip_stream)
+{
+    int rc;
+    if (!status_args_ok(f, act_off, act_prompt, act_gen, act_rem, n_active, q_off, q_prompt, q_len,
+                        n_queued, &rc))
+        return rc;
+    if (n_active > 0 && !out_act_finish) return GR_ERR_INVALID_ARG;
+    StatusIn in{};
+    in.act_off = act_off; in.act_prompt = act_prompt; in.act_gen = act_gen; in.act_rem = act_rem;
+    in.q_off = q_off; in.q_prompt = q_prompt; in.q_len = q_len;
+    in.n_active = n_active; in.n_queued = n_queued;
+    in.out_act_finish = out_act_finish; in.out_q_finish = out_q_finish;
+    in.out_d = out_d; in.out_rank = out_rank;
+    return launch_status(f, in, static_cast<hipStream_t>(hip_stream));
+}
+
+int gr_score_route(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_t* pred_len,
+                   const float* budget, const int32_t* exclude_inst, int32_t* out_inst,
+                   float* out_slack, uint8_t* out_fallback, float* out_T, void* hip_stream)
+{
+    if (!f || n_req < 0) return GR_ERR_INVALID_ARG;
+    if (!f->has_status) return GR_ERR_NO_STATUS;
+    if (n_req == 0) return GR_OK;
+    if (!ctx0 || !pred_len || !budget || !out_inst || !out_slack) return GR_ERR_INVALID_ARG;
+    if (n_req > f->max_requests) return GR_ERR_TOO_LARGE;
+    ReqSrc src{};
+    src.ctx0 = ctx0; src.pred_len = pred_len; src.budget = budget; src.exclude = exclude_inst;
+    src.n = n_req;
+    ScoreOut o{};
+    o.inst = out_inst; o.slack = out_slack; o.fallback = out_fallback; o.T = out_T;
+    return launch_score(f, src, false, o, static_cast<hipStream_t>(hip_stream));
+}
+
+int gr_risk_scan(gr_fleet* f, const int32_t* act_off, const int32_t* act_prompt,
+                 const int32_t* act_gen, const int32_t* act_rem_refreshed, int64_t n_active,
+                 const int32_t* q_off, const int32_t* q_prompt, const int32_t* q_len,
+                 int64_t n_queued, const float* act_budget, uint8_t* out_flag, float* out_finish,
+                 int32_t* out_target, float* out_target_slack, int32_t* out_n_flagged,
+                 void* hip_stream)
+{
+    int rc;
+    if (!status_args_ok(f, act_off, act_prompt, act_gen, act_rem_refreshed, n_active, q_off, q_prompt,
+                        q_len, n_queued, &rc))
+        return rc;
+    if (n_active > 0 && (!act_budget || !out_flag || !out_finish || !out_target || !out_target_slack))
+        return GR_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    StatusIn in{};
+    in.act_off = act_off; in.act_prompt = act_prompt; in.act_gen = act_gen; in.act_rem = act_rem_refreshed;
+    in.q_off = q_off; in.q_prompt = q_prompt; in.q_len = q_len;
+    in.act_budget = act_budget;
+    in.n_active = n_active; in.n_queued = n_queued;
+    in.out_act_finish = out_finish; in.out_flag = out_flag;
+    rc = launch_status(f, in, s);
+    if (rc != GR_OK) return rc;
+    ReqSrc src{};
+    src.act_prompt = act_prompt; src.act_gen = act_gen; src.act_rem = act_rem_refreshed;
+    src.act_inst = f->act_inst; src.flag = out_flag; src.act_budget = act_budget;
+    src.n = n_active;
+    ScoreOut o{};
+    o.inst = out_target; o.slack = out_target_slack; o.n_selected = out_n_flagged;
+    return launch_score(f, src, true, o, s);
+}
+
+int gr_device_status(gr_fleet* f, int32_t* out_bits)
+{
+    if (!f || !out_bits) return GR_ERR_INVALID_ARG;
+    if (hipDeviceSynchronize() != hipSuccess) return GR_ERR_HIP;
+    int v = 0;
+    if (hipMemcpy(&v, f->counters, sizeof(int), hipMemcpyDeviceToHost) != hipSuccess) return GR_ERR_HIP;
+    *out_bits = v;
+    return GR_OK;
+}
+
+int gr_profile_enable(gr_fleet* f, int32_t max_launches)
+{
+    if (!f || max_launches < 0) return GR_ERR_INVALID_ARG;
+    Profiler& p = f->prof;
+    if (hipDeviceSynchronize() != hipSuccess) return GR_ERR_HIP;
+    p.ids.clear();
+    p.on = max_launches > 0;
+    p.ids.reserve((size_t)max_launches);
+    while (p.events.size() < (size_t)max_launches * 2) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { p.on = false; return GR_ERR_HIP; }
+        p.events.push_back(e);
+    }
+    return GR_OK;
+}
+
+int gr_profile_read(gr_fleet* f, int32_t n_kernels, double* total_ms, int64_t* launches)
+{
+    if (!f || n_kernels < 0 || (n_kernels > 0 && (!total_ms || !launches))) return GR_ERR_INVALID_ARG;
+    if (hipDeviceSynchronize() != hipSuccess) return GR_ERR_HIP;
+    Profiler& p = f->prof;
+    for (int k = 0; k < n_kernels; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
+    for (size_t i = 0; i < p.ids.size(); ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.events[2 * i], p.events[2 * i + 1]) != hipSuccess) return GR_ERR_HIP;
+        if (p.ids[i] < n_kernels) { total_ms[p.ids[i]] += ms; launches[p.ids[i]] += 1; }
+    }
+    p.ids.clear();
+    return GR_OK;
+}
+
+int32_t gr_profile_kernel_count(void) { return kNumKernels; }
+
+const char* gr_profile_kernel_name(int32_t id)
+{
+    return id >= 0 && id < kNumKernels ? kKernelNames[id] : "";
+}
+
+const char* gr_strerror(int code)
+{
+    switch (code) {
+        case GR_OK: return "ok";
+        case GR_ERR_INVALID_ARG: return "invalid argument";
+        case GR_ERR_TOO_LARGE: return "size exceeds what the handle was created for or a hard limit";
+        case GR_ERR_HIP: return "HIP runtime error";
+        case GR_ERR_NO_STATUS: return "no status built yet: call gr_build_status or gr_risk_scan first";
+        case GR_ERR_NOMEM: return "out of memory";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,192 @@
+// Internal declarations shared by the source files of libgoodroute (gfx950).
+// The public interface and the time model are in goodroute.h.
+//
+// Closed form used throughout.  Let instance g hold N requests with remaining
+// lengths R_i and contexts c_i.  Under continuous batching with step time
+// alpha + beta*B + gamma*C, the time of its next L steps is
+//     W_g(L) = alpha*L + beta*sum_i min(R_i,L) + gamma*sum_i [c_i*min(R_i,L) + tri(min(R_i,L))]
+// with tri(x) = x(x-1)/2, because request i is in the batch for min(R_i,L) of
+// those steps and its context at its s-th step is c_i + s - 1.  With the
+// requests sorted by R and k = #{i : R_i <= L} this is
+//     W_g(L) = alpha*L + beta*(Y_k + (N-k)*L) + gamma*(X_k + L*S_{k+1} + (N-k)*tri(L))
+//     Y_k = sum_{i<=k} R_i,  X_k = sum_{i<=k} (c_i*R_i + tri(R_i)),  S_{k+1} = sum_{i>k} c_i,
+// three integer prefix sums, exact in 64-bit.  A request r routed to g is one
+// more batch member with R = L, so Eq. 2 reads
+//     T(r,g) = q_g + delta*c0 + W_g(L) + beta*L + gamma*(c0*L + tri(L))
+//            = E_g(L) + c0 * kappa_g(L),
+//     E_g(L)     = q_g + W_g(L) + beta*L + gamma*tri(L)      (instance and length only)
+//     kappa_g(L) = delta + gamma*L.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "goodroute.h"
+
+namespace gr {
+
+constexpr int kBlock = 256;
+constexpr int kWave = 64;
+constexpr int kWaves = kBlock / kWave;
+constexpr int kMaxEntries = 8192;
+constexpr int kMaxClasses = 64;
+constexpr int kMaxLen = 32767;     // one LDS counter per length in the grouping kernels
+constexpr int kTileReq = 16;       // requests of one length scored together by one wave
+constexpr int kGroupItems = 16;    // requests per thread in the grouping kernels
+constexpr int kGroupChunk = kBlock * kGroupItems;
+constexpr int kMemoU = 256;        // lengths per workgroup of the memo kernel
+constexpr int kMemoP = 16;         // instances per workgroup of the memo kernel
+
+struct ClassCoef {
+    double delta, alpha, beta, gamma;
+};
+
+// One request in grouped order.
+struct ReqRec {
+    float c0;   // tokens to prefill
+    float D;    // budget
+    int pex;    // excluded instance as a position in capability order, -1 none
+    int orig;   // index in the caller's arrays
+};
+
+// Where a batch of requests comes from: the caller's arrays (routing) or the
+// flagged active requests (migration).
+struct ReqSrc {
+    const int *ctx0, *pred_len;
+    const float* budget;
+    const int* exclude;
+    const int *act_prompt, *act_gen, *act_rem, *act_inst;
+    const uint8_t* flag;
+    const float* act_budget;
+    int64_t n;
+};
+
+struct ScoreOut {
+    int* inst;
+    float* slack;
+    uint8_t* fallback;   // may be null
+    float* T;            // may be null: every pair's latency
+    int* n_selected;     // may be null: number of requests scored
+};
+
+enum KernelId {
+    kBuild = 0, kRankCount, kRankFinal, kHistRoute, kScanRoute, kScatterRoute, kMemoRoute, kTileRoute,
+    kHistMigrate, kScanMigrate, kScatterMigrate, kMemoMigrate, kTileMigrate, kNumKernels
+};
+
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> events;  // pairs: start, stop
+    std::vector<int> ids;            // kernel id of each recorded pair
+};
+
+}  // namespace gr
+
+struct gr_fleet {
+    gr::Profiler prof;
+    int n_inst = 0, n_class = 0, max_entries = 0, max_len = 0;
+    int64_t max_requests = 0;
+    int64_t max_active = 0;
+    int64_t req_cap = 0;   // requests one scoring pass may hold
+    int idx_bits = 0, key_bits = 0;
+    int ncap = 0;          // entries the sort buffers hold (multiple of 64)
+    int tstride = 0;       // table entries per instance, max_entries + 1
+    int m_pad = 0;         // instances rounded up to a multiple of 64
+    int bins = 0;          // max_len + 1
+    int64_t row_cap = 0;   // rows of the memo table
+    int device = 0;
+    bool has_status = false;
+    // device memory: fleet description
+    gr::ClassCoef* cls = nullptr;
+    int* inst_class = nullptr;
+    // per-instance tables written by the status build
+    int* tabR = nullptr;     // [M][tstride] sorted remaining lengths, entry 0 = 0
+    float* tabG = nullptr;   // [M][tstride] beta*Y_k + gamma*X_k
+    float* tabS = nullptr;   // [M][tstride] S_{k+1}
+    int* hN = nullptr;       // [M] entries per instance
+    double* hQ = nullptr;    // [M] q_g
+    double* hD = nullptr;    // [M] d_g
+    int* rank_acc = nullptr; // [M] partial counts of the rank kernels
+    int* rank = nullptr;     // [M]
+    int* order = nullptr;    // [m_pad] order[rank[g]] = g
+    int* act_inst = nullptr; // [max_active] instance of each active request
+    int* counters = nullptr; // [1] GR_DEV_* bits
+    // scoring workspace
+    int* len_cnt = nullptr;   // [bins] requests per length; all zero between calls
+    int* len_base = nullptr;  // [bins] next free slot of each length in grouped order
+    int* row_len = nullptr;   // [row_cap] the distinct lengths, ascending
+    int* row_off = nullptr;   // [row_cap+1] first request of each distinct length
+    int* tile_off = nullptr;  // [row_cap+1] first tile of each distinct length
+    int* totals = nullptr;    // [4] requests, distinct lengths, tiles
+    gr::ReqRec* recs = nullptr;  // [req_cap] requests in grouped order
+    float2* memo = nullptr;      // [row_cap][m_pad] (E, kappa) per distinct length and position
+};
+
+namespace gr {
+
+// Brackets one kernel launch with a pair of events when timing is switched on.
+struct ProfScope {
+    Profiler& p;
+    hipStream_t s;
+    size_t slot = SIZE_MAX;
+    ProfScope(gr_fleet* f, int id, hipStream_t stream) : p(f->prof), s(stream)
+    {
+        if (!p.on || (p.ids.size() + 1) * 2 > p.events.size()) return;
+        slot = p.ids.size();
+        p.ids.push_back(id);
+        (void)hipEventRecord(p.events[2 * slot], s);
+    }
+    ~ProfScope()
+    {
+        if (slot != SIZE_MAX) (void)hipEventRecord(p.events[2 * slot + 1], s);
+    }
+};
+
+struct StatusIn {
+    const int *act_off, *act_prompt, *act_gen, *act_rem;
+    const int *q_off, *q_prompt, *q_len;
+    const float* act_budget;  // null unless flags are wanted
+    int64_t n_active, n_queued;
+    float *out_act_finish, *out_q_finish;
+    double* out_d;
+    int* out_rank;
+    uint8_t* out_flag;
+};
+
+// status.hip
+size_t status_lds_bytes(const gr_fleet* f);
+int status_prepare(gr_fleet* f);   // one-time kernel attributes
+int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s);
+
+// score.hip
+size_t score_lds_bytes(const gr_fleet* f);
+int score_prepare(gr_fleet* f);
+int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& out, hipStream_t s);
+
+// ------------------------------------------------------------------ wave helpers
+__device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }
+
+template <typename T>
+__device__ inline T wave_sum(T v)
+{
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, kWave);
+    return v;
+}
+
+template <typename T>
+__device__ inline T wave_incl_scan(T v)
+{
+    const int lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        T o = __shfl_up(v, d, kWave);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+}  // namespace gr
