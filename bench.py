@@ -177,11 +177,11 @@ def main():
             # two launches per step: plain build, and the scan's rebuild with budget + flag
             by = entries * (BUILD_BYTES_PER_ENTRY + SCAN_EXTRA_BYTES_PER_ENTRY / 2)
             k.update(bound="hbm", achieved=by / (avg_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
-        else:
-            continue
-        k["frac"] = k["achieved"] / k["peak"]
+        if "achieved" in k:
+            k["frac"] = k["achieved"] / k["peak"]
         kernels[name] = k
-    dominant = max(kernels, key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
+    dominant = max((n for n in kernels if "bound" in kernels[n]),
+                   key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
     dk = kernels[dominant]
     roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
                 "unit": dk["unit"], "frac": dk["frac"], "traffic": None,

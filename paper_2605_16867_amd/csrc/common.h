@@ -31,7 +31,7 @@ namespace gr {
 constexpr int kBlock = 256;
 constexpr int kWave = 64;
 constexpr int kWaves = kBlock / kWave;
-constexpr int kMaxEntries = 8192;
+constexpr int kMaxEntries = 2048;
 constexpr int kMaxClasses = 64;
 constexpr int kMaxLen = 32767;     // one LDS counter per length in the grouping kernels
 constexpr int kTileReq = 16;       // requests of one length scored together by one wave

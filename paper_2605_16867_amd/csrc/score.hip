@@ -83,41 +83,48 @@ __device__ inline unsigned long long block_incl_scan(unsigned long long v, unsig
     return v + before;
 }
 
-// One workgroup walks the length histogram: the first slot of each length in
-// grouped order, the list of lengths present ("rows"), the first tile of each
-// row (a tile = up to kTileReq requests of one length), and the totals.  The
-// histogram is cleared for the next call.
+// One workgroup walks the length histogram (copied to LDS; a thread owns a run
+// of consecutive lengths): the first slot of each length in grouped order, the
+// list of lengths present ("rows"), the first tile of each row (a tile = up to
+// kTileReq requests of one length), and the totals.  The histogram is cleared
+// for the next call.
 __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, int* __restrict__ len_base,
                                                      int* __restrict__ row_len, int* __restrict__ row_off,
                                                      int* __restrict__ tile_off, int* __restrict__ totals,
                                                      int* __restrict__ out_n, int bins)
 {
+    extern __shared__ uint32_t lds[];
+    int* cnt = reinterpret_cast<int*>(lds);
     __shared__ unsigned long long ws[kScanBlock / kWave];
     const int tid = threadIdx.x;
-    unsigned long long c_req_tile = 0;   // requests in the low half, tiles in the high half
-    unsigned long long c_row = 0;
-    for (int base = 0; base < bins; base += kScanBlock) {
-        const int L = base + tid;
-        int c = 0;
-        if (L < bins) { c = len_cnt[L]; len_cnt[L] = 0; }
-        const unsigned long long tiles = (unsigned)(c + kTileReq - 1) / kTileReq;
-        const unsigned long long mine = (unsigned long long)(unsigned)c | (tiles << 32);
-        unsigned long long tot1, tot2;
-        const unsigned long long in1 = block_incl_scan(mine, ws, tot1);
-        const unsigned long long in2 = block_incl_scan(c > 0 ? 1ull : 0ull, ws, tot2);
-        const unsigned long long ex1 = in1 - mine + c_req_tile;
-        if (L < bins) len_base[L] = (int)(ex1 & 0xFFFFFFFFull);
-        if (c > 0) {
-            const int u = (int)(in2 - 1 + c_row);
-            row_len[u] = L;
-            row_off[u] = (int)(ex1 & 0xFFFFFFFFull);
-            tile_off[u] = (int)(ex1 >> 32);
-        }
-        c_req_tile += tot1;
-        c_row += tot2;
+    for (int i = tid; i < bins; i += kScanBlock) { cnt[i] = len_cnt[i]; len_cnt[i] = 0; }
+    __syncthreads();
+    const int per = ((bins + kScanBlock - 1) / kScanBlock) | 1;   // odd: no LDS bank conflicts
+    const int i0 = min(tid * per, bins), i1 = min(i0 + per, bins);
+    unsigned long long mine = 0, rows = 0;     // requests in the low half, tiles in the high half
+    for (int i = i0; i < i1; ++i) {
+        const unsigned c = (unsigned)cnt[i];
+        mine += (unsigned long long)c | ((unsigned long long)((c + kTileReq - 1) / kTileReq) << 32);
+        rows += c > 0;
     }
+    unsigned long long tot1, tot2;
+    unsigned long long run = block_incl_scan(mine, ws, tot1) - mine;
+    int u = (int)(block_incl_scan(rows, ws, tot2) - rows);
+    for (int i = i0; i < i1; ++i) {
+        const unsigned c = (unsigned)cnt[i];
+        cnt[i] = (int)(run & 0xFFFFFFFFull);
+        if (c) {
+            row_len[u] = i;
+            row_off[u] = (int)(run & 0xFFFFFFFFull);
+            tile_off[u] = (int)(run >> 32);
+            ++u;
+        }
+        run += (unsigned long long)c | ((unsigned long long)((c + kTileReq - 1) / kTileReq) << 32);
+    }
+    __syncthreads();
+    for (int i = tid; i < bins; i += kScanBlock) len_base[i] = cnt[i];
     if (tid == 0) {
-        const int n = (int)(c_req_tile & 0xFFFFFFFFull), U = (int)c_row, NT = (int)(c_req_tile >> 32);
+        const int n = (int)(tot1 & 0xFFFFFFFFull), U = (int)tot2, NT = (int)(tot1 >> 32);
         row_off[U] = n;
         tile_off[U] = NT;
         totals[0] = n; totals[1] = U; totals[2] = NT;
@@ -195,62 +202,73 @@ struct MemoArgs {
 };
 
 // (E, kappa) for kMemoU distinct lengths x kMemoP instances (consecutive
-// positions of the capability order) per workgroup.  A wave takes one instance
-// at a time, its lanes the lengths, and finds k = #{R_i <= L} by binary search
-// in the instance's sorted lengths; the tile is turned in LDS so that the table
-// is written in rows of positions.
-__global__ __launch_bounds__(kBlock) void k_memo(MemoArgs a)
+// positions of the capability order) per workgroup of kMemoP waves.  A wave
+// takes one instance: it copies the instance's sorted lengths to LDS, its lanes
+// take the request lengths and find k = #{R_i <= L} by binary search there; the
+// tile is turned in LDS so that the table is written in rows of positions.
+constexpr int kMemoBlock = kMemoP * kWave;
+
+__global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
 {
+    extern __shared__ uint32_t lds[];
     __shared__ float2 tile[kMemoU][kMemoP + 1];
     const int U = a.totals[1];
     const int u0 = blockIdx.y * kMemoU;
     if (u0 >= U) return;
     const int p0 = blockIdx.x * kMemoP;
-    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
+    const int tid = threadIdx.x, lane = lane_id(), pi = tid / kWave;
+    int* sR = reinterpret_cast<int*>(lds) + (size_t)pi * a.tstride;   // this wave's copy
     constexpr int kPerLane = kMemoU / kWave;
-    int Lv[kPerLane];
+    const int p = p0 + pi;
+    const int g = p < a.n_inst ? a.order[p] : -1;
+    if (g >= 0) {
+        const int N = a.hN[g];
+        const int* R = a.tabR + (size_t)g * a.tstride;
+        for (int k = lane; k <= N; k += kWave) sR[k] = R[k];
+        int Lv[kPerLane];
 #pragma unroll
-    for (int i = 0; i < kPerLane; ++i) {
-        const int u = u0 + lane + kWave * i;
-        Lv[i] = u < U ? a.row_len[u] : 0;
-    }
-#pragma unroll 1
-    for (int j = 0; j < kMemoP / kWaves; ++j) {
-        const int pi = wave * (kMemoP / kWaves) + j;
-        const int p = p0 + pi;
-        const int g = p < a.n_inst ? a.order[p] : -1;
-        if (g >= 0) {
-            const int N = a.hN[g];
-            const double q = a.hQ[g];
-            const ClassCoef cc = a.cls[a.inst_class[g]];
-            const int* R = a.tabR + (size_t)g * a.tstride;
-            const float* G = a.tabG + (size_t)g * a.tstride;
-            const float* S = a.tabS + (size_t)g * a.tstride;
-#pragma unroll
-            for (int i = 0; i < kPerLane; ++i) {
-                const int L = Lv[i];
-                int lo = 0, hi = N;
-                while (lo < hi) {
-                    const int mid = (lo + hi + 1) >> 1;
-                    if (R[mid] <= L) lo = mid; else hi = mid - 1;
-                }
-                const double Ld = (double)L, n1 = (double)(N - lo + 1);
-                const double tri = Ld * (Ld - 1.0) * 0.5;
-                const double E = q + cc.alpha * Ld + cc.beta * (n1 * Ld) + (double)G[lo]
-                                 + cc.gamma * (Ld * (double)S[lo] + n1 * tri);
-                tile[lane + kWave * i][pi] = make_float2((float)E, (float)(cc.delta + cc.gamma * Ld));
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < kPerLane; ++i)
-                tile[lane + kWave * i][pi] = make_float2(__builtin_inff(), 0.f);
+        for (int i = 0; i < kPerLane; ++i) {
+            const int u = u0 + lane + kWave * i;
+            Lv[i] = u < U ? a.row_len[u] : 0;
         }
+        const double q = a.hQ[g];
+        const ClassCoef cc = a.cls[a.inst_class[g]];
+        const float* G = a.tabG + (size_t)g * a.tstride;
+        const float* S = a.tabS + (size_t)g * a.tstride;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        int kk[kPerLane];
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            int lo = 0, hi = N;
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (sR[mid] <= Lv[i]) lo = mid; else hi = mid - 1;
+            }
+            kk[i] = lo;
+        }
+        float Gv[kPerLane], Sv[kPerLane];
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) { Gv[i] = G[kk[i]]; Sv[i] = S[kk[i]]; }
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const double Ld = (double)Lv[i], n1 = (double)(N - kk[i] + 1);
+            const double tri = Ld * (Ld - 1.0) * 0.5;
+            const double E = q + cc.alpha * Ld + cc.beta * (n1 * Ld) + (double)Gv[i]
+                             + cc.gamma * (Ld * (double)Sv[i] + n1 * tri);
+            tile[lane + kWave * i][pi] = make_float2((float)E, (float)(cc.delta + cc.gamma * Ld));
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i)
+            tile[lane + kWave * i][pi] = make_float2(__builtin_inff(), 0.f);
     }
     __syncthreads();
     const int col = tid % kMemoP;
-#pragma unroll 4
-    for (int it = 0; it < kMemoU * kMemoP / kBlock; ++it) {
-        const int ul = tid / kMemoP + (kBlock / kMemoP) * it;
+#pragma unroll
+    for (int it = 0; it < kMemoU * kMemoP / kMemoBlock; ++it) {
+        const int ul = tid / kMemoP + (kMemoBlock / kMemoP) * it;
         const int u = u0 + ul;
         if (u < U) a.memo[(size_t)u * a.m_pad + p0 + col] = tile[ul][col];
     }
@@ -273,13 +291,134 @@ __device__ inline float readlane_f(float v, int lane)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
-__device__ inline float wave_min(float v)
+// One step of a wave-wide minimum: combine with the lane selected by a DPP control.
+template <int kCtrl, int kRowMask>
+__device__ inline float min_dpp(float v)
 {
-#pragma unroll
-    for (int d = kWave / 2; d > 0; d >>= 1) v = fminf(v, __shfl_xor(v, d, kWave));
-    return v;
+    const int t = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), kCtrl, kRowMask, 0xf, false);
+    const float o = __int_as_float(t);
+    return o < v ? o : v;
 }
 
+// Minimum over the 64 lanes (no NaNs among the inputs).  Prefix minima inside
+// each row of 16 lanes (row_shr 1, 2, 4, 8), then lane 15 of rows 0 and 2 into
+// rows 1 and 3, then lane 31 into rows 2 and 3: lane 63 holds the result.
+__device__ inline float wave_min(float v)
+{
+    v = min_dpp<0x111, 0xf>(v);
+    v = min_dpp<0x112, 0xf>(v);
+    v = min_dpp<0x114, 0xf>(v);
+    v = min_dpp<0x118, 0xf>(v);
+    v = min_dpp<0x142, 0xa>(v);
+    v = min_dpp<0x143, 0xc>(v);
+    return readlane_f(v, kWave - 1);
+}
+
+struct TileState {
+    float c0[kTileReq];     // same in every lane: tokens to prefill of request j (0 past the tile's last request)
+    float D[kTileReq];      // same in every lane: budget of request j; -inf once its instance is found
+    float minT[kTileReq];   // per lane: smallest T of request j over the blocks seen
+    int minB[kTileReq];     // per lane: the block it was seen in
+    unsigned notfound;      // bit j: request j has no feasible instance so far
+    int foundP;             // lane j: position of request j's first feasible instance
+    float foundT;           // lane j: its T
+};
+
+// Request j has feasible instances in block b (lanes `feas`): the first one in
+// capability order is its just-enough choice.
+__device__ inline void record_found(TileState& st, int j, int b, unsigned long long feas, float T, int lane)
+{
+    const int fl = __ffsll((long long)feas) - 1;
+    const float Tf = readlane_f(T, fl);
+    if (lane == j) { st.foundP = b * kWave + fl; st.foundT = Tf; }
+    st.notfound &= ~(1u << j);
+    st.D[j] = -__builtin_inff();
+}
+
+// One block of 64 instances against the tile's requests: per pair one
+// multiply-add, the feasibility compare and the running minimum (5 vector
+// operations).  Feasibility is only OR-ed here and looked at per request when
+// the block has any.
+__device__ inline void block_step(TileState& st, int b, float2 cur, int lane)
+{
+    unsigned long long anyf = 0;
+#pragma unroll
+    for (int j = 0; j < kTileReq; ++j) {
+        const float T = fmaf(st.c0[j], cur.y, cur.x);
+        anyf |= __ballot(T <= st.D[j]);
+        const bool lt = T < st.minT[j];
+        st.minB[j] = lt ? b : st.minB[j];
+        st.minT[j] = lt ? T : st.minT[j];
+    }
+    if (anyf) {
+        // rare: recomputed from opaque copies so that nothing of it stays live in the loop above
+        asm volatile("" : "+v"(cur.x), "+v"(cur.y));
+#pragma unroll
+        for (int j = 0; j < kTileReq; ++j) {
+            const float T = fmaf(st.c0[j], cur.y, cur.x);
+            const unsigned long long feas = __ballot(T <= st.D[j]);
+            if (feas) {
+                // the first feasible instance in capability order is the just-enough choice
+                const int fl = __ffsll((long long)feas) - 1;
+                const float Tf = readlane_f(T, fl);
+                if (lane == j) { st.foundP = b * kWave + fl; st.foundT = Tf; }
+                st.notfound &= ~(1u << j);
+                st.D[j] = -__builtin_inff();
+            }
+        }
+    }
+}
+
+// Smallest T of one request over the wave: position (ties to the lowest instance) and value.
+__device__ inline void wave_argmin(float minT, int minB, const int* __restrict__ order, int& pos, float& val)
+{
+    const float Tm = wave_min(minT);
+    unsigned long long cand = __ballot(minT == Tm && Tm < __builtin_inff());
+    int bp = -1, bg = 0x7fffffff;
+    while (cand) {
+        const int l = __ffsll((long long)cand) - 1;
+        cand &= cand - 1;
+        const int p = __builtin_amdgcn_readlane(minB, l) * kWave + l;
+        const int g = order[p];
+        if (g < bg) { bg = g; bp = p; }
+    }
+    pos = bp;
+    val = Tm;
+}
+
+// One request on its own against all instances but the one at position `pex`:
+// used when the choice made without the exclusion fell on the excluded instance.
+__device__ inline void rescan_excluding(const float2* __restrict__ row, int nblk, float c0, float D, int pex,
+                                        const int* __restrict__ order, int lane, int& pos, float& val, bool& found)
+{
+    float minT = __builtin_inff();
+    int minB = 0;
+    found = false;
+    pos = -1;
+    val = 0.f;
+    for (int b = 0; b < nblk; ++b) {
+        const float2 cur = row[b * kWave + lane];
+        float T = fmaf(c0, cur.y, cur.x);
+        if (b * kWave + lane == pex) T = __builtin_inff();
+        const unsigned long long feas = __ballot(T <= D);
+        if (feas) {
+            const int fl = __ffsll((long long)feas) - 1;
+            pos = b * kWave + fl;
+            val = readlane_f(T, fl);
+            found = true;
+            return;
+        }
+        const bool lt = T < minT;
+        minB = lt ? b : minB;
+        minT = lt ? T : minT;
+    }
+    wave_argmin(minT, minB, order, pos, val);
+}
+
+// One wave per tile: up to kTileReq requests of one length against all
+// instances, 64 instances (one block of the capability order) per step.
+// Excluded instances are ignored in the main pass; a request whose choice
+// falls on its excluded instance is scored again on its own.
 template <bool kWriteT>
 __global__ __launch_bounds__(kBlock) void k_tile(TileArgs a)
 {
@@ -292,92 +431,95 @@ __global__ __launch_bounds__(kBlock) void k_tile(TileArgs a)
     const int t = bid * kWaves + wave;
     if (t >= NT) return;
 
-    int lo = 0, hi = U - 1;                 // row of this tile: last u with tile_off[u] <= t
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (a.tile_off[mid] <= t) lo = mid; else hi = mid - 1;
+    // row of this tile: the last u with tile_off[u] <= t, by a 64-way search
+    int lo = 0, len = U;
+    while (len > 1) {
+        const int stride = (len + kWave - 1) / kWave;
+        const int idx = lo + lane * stride;
+        const bool le = idx < lo + len && a.tile_off[idx] <= t;
+        const int cnt = __popcll(__ballot(le));
+        const int nlo = lo + (cnt - 1) * stride;
+        len = min(stride, lo + len - nlo);
+        lo = nlo;
     }
     const int u = lo;
     const int r0 = a.row_off[u] + (t - a.tile_off[u]) * kTileReq;
     const int nreq = min(kTileReq, a.row_off[u + 1] - r0);
 
+    // lanes past the tile's last request carry a dummy that is never feasible and never reported
     ReqRec rec;
     rec.c0 = 0.f; rec.D = -__builtin_inff(); rec.pex = -1; rec.orig = -1;
     if (lane < nreq) rec = a.recs[r0 + lane];
-    float c0[kTileReq], D[kTileReq], minT[kTileReq];
-    int minB[kTileReq];
+    const float Dc = fminf(rec.D, FLT_MAX);   // padded positions hold +inf and must stay infeasible
+    TileState st;
 #pragma unroll
     for (int j = 0; j < kTileReq; ++j) {
-        c0[j] = readlane_f(rec.c0, j);
-        D[j] = fminf(readlane_f(rec.D, j), FLT_MAX);   // padded positions hold +inf and must stay infeasible
-        minT[j] = __builtin_inff();
-        minB[j] = 0;
+        st.c0[j] = readlane_f(rec.c0, j);
+        st.D[j] = readlane_f(Dc, j);
+        // keep both in vector registers: the scalar file is too small for 16 requests
+        asm volatile("" : "+v"(st.c0[j]), "+v"(st.D[j]));
+        st.minT[j] = __builtin_inff();
+        st.minB[j] = 0;
     }
-    unsigned notfound = (1u << nreq) - 1u;
-    int foundP = -1;         // lane j: position of request j's first feasible instance
-    float foundT = 0.f;
+    st.notfound = (1u << nreq) - 1u;
+    st.foundP = -1;
+    st.foundT = 0.f;
 
-    const float2* row = a.memo + (size_t)u * a.m_pad;
+    const float2* __restrict__ row = a.memo + (size_t)u * a.m_pad;
     const int nblk = a.m_pad / kWave;
-    const int ex_blk = rec.pex >= 0 ? rec.pex / kWave : -1;
     float2 next = row[lane];
     for (int b = 0; b < nblk; ++b) {
         const float2 cur = next;
         if (b + 1 < nblk) next = row[(b + 1) * kWave + lane];
-        const unsigned hit = (unsigned)__ballot(ex_blk == b);   // requests whose excluded instance is here
-        int g_lane = -1;
-        if (kWriteT) g_lane = a.order[b * kWave + lane];
-#pragma unroll
-        for (int j = 0; j < kTileReq; ++j) {
-            if (j < nreq) {
-                float T = fmaf(c0[j], cur.y, cur.x);
-                if (kWriteT) {
-                    const int orig = __builtin_amdgcn_readlane(rec.orig, j);
-                    if (g_lane >= 0) a.out_T[(size_t)orig * a.n_inst + g_lane] = T;
-                }
-                if ((hit >> j) & 1u) {
-                    const int ex_lane = __builtin_amdgcn_readlane(rec.pex, j) & (kWave - 1);
-                    if (lane == ex_lane) T = __builtin_inff();
-                }
-                const unsigned long long feas = __ballot(T <= D[j]);
-                if (feas && ((notfound >> j) & 1u)) {
-                    const int fl = __ffsll((long long)feas) - 1;
-                    notfound &= ~(1u << j);
-                    const float Tf = readlane_f(T, fl);
-                    if (lane == j) { foundP = b * kWave + fl; foundT = Tf; }
-                }
-                if (T < minT[j]) { minT[j] = T; minB[j] = b; }
-            }
-        }
+        block_step(st, b, cur, lane);
     }
 
-    // fallback for requests with no feasible instance: smallest T, ties to the lowest instance
+    // requests with no feasible instance fall back to the smallest T
     int bestP = -1;
     float bestT = 0.f;
 #pragma unroll
     for (int j = 0; j < kTileReq; ++j) {
-        if (j < nreq && ((notfound >> j) & 1u)) {
-            const float Tm = wave_min(minT[j]);
-            unsigned long long cand = __ballot(minT[j] == Tm && Tm < __builtin_inff());
-            int bp = -1, bg = 0x7fffffff;
-            while (cand) {
-                const int l = __ffsll((long long)cand) - 1;
-                cand &= cand - 1;
-                const int p = __builtin_amdgcn_readlane(minB[j], l) * kWave + l;
-                const int g = a.order[p];
-                if (g < bg) { bg = g; bp = p; }
-            }
-            if (lane == j) { bestP = bp; bestT = Tm; }
+        if ((st.notfound >> j) & 1u) {
+            int bp;
+            float bt;
+            wave_argmin(st.minT[j], st.minB[j], a.order, bp, bt);
+            if (lane == j) { bestP = bp; bestT = bt; }
         }
     }
+    bool found = !((st.notfound >> lane) & 1u);
+    int p = found ? st.foundP : bestP;
+    float T = found ? st.foundT : bestT;
+
+    // choices that fell on the request's excluded instance
+    unsigned long long redo = __ballot(lane < nreq && rec.pex >= 0 && p == rec.pex);
+    while (redo) {
+        const int j = __ffsll((long long)redo) - 1;
+        redo &= redo - 1;
+        int rp;
+        float rt;
+        bool rf;
+        rescan_excluding(row, nblk, readlane_f(rec.c0, j), readlane_f(Dc, j),
+                         __builtin_amdgcn_readlane(rec.pex, j), a.order, lane, rp, rt, rf);
+        if (lane == j) { p = rp; T = rt; found = rf; }
+    }
+
     if (lane < nreq) {
-        const bool found = !((notfound >> lane) & 1u);
-        const int p = found ? foundP : bestP;
-        const float T = found ? foundT : bestT;
         const int g = p >= 0 ? a.order[p] : -1;
         a.out_inst[rec.orig] = g;
         a.out_slack[rec.orig] = g >= 0 ? rec.D - T : 0.f;
         if (a.out_fallback) a.out_fallback[rec.orig] = !found;
+    }
+
+    if (kWriteT) {   // every pair's latency, for checking: same arithmetic, exclusions not applied
+        for (int b = 0; b < nblk; ++b) {
+            const float2 cur = row[b * kWave + lane];
+            const int g_lane = a.order[b * kWave + lane];
+            for (int j = 0; j < nreq; ++j) {
+                const int orig = __builtin_amdgcn_readlane(rec.orig, j);
+                const float Tj = fmaf(readlane_f(rec.c0, j), cur.y, cur.x);
+                if (g_lane >= 0) a.out_T[(size_t)orig * a.n_inst + g_lane] = Tj;
+            }
+        }
     }
 }
 
@@ -392,13 +534,21 @@ bool set_lds(K kernel, size_t bytes)
 
 }  // namespace
 
-size_t score_lds_bytes(const gr_fleet* f) { return (size_t)f->bins * 4; }
+size_t memo_lds_bytes(const gr_fleet* f) { return (size_t)kMemoP * f->tstride * 4; }
+
+size_t score_lds_bytes(const gr_fleet* f)
+{
+    const size_t group = (size_t)f->bins * 4;
+    const size_t memo = memo_lds_bytes(f) + sizeof(float2) * kMemoU * (kMemoP + 1);
+    return group > memo ? group : memo;
+}
 
 int score_prepare(gr_fleet* f)
 {
     const size_t hist = (size_t)((f->bins + 1) / 2) * 4, scat = (size_t)f->bins * 4;
     const bool ok = set_lds(k_hist<false>, hist) && set_lds(k_hist<true>, hist) &&
-                    set_lds(k_scatter<false>, scat) && set_lds(k_scatter<true>, scat);
+                    set_lds(k_scatter<false>, scat) && set_lds(k_scatter<true>, scat) &&
+                    set_lds(k_scan, scat) && set_lds(k_memo, memo_lds_bytes(f));
     return ok ? GR_OK : GR_ERR_HIP;
 }
 
@@ -420,7 +570,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     }
     {
         ProfScope ps(f, kScanRoute + off, s);
-        hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanBlock), 0, s, f->len_cnt, f->len_base, f->row_len,
+        hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanBlock), scat_lds, s, f->len_cnt, f->len_base, f->row_len,
                            f->row_off, f->tile_off, f->totals, out.n_selected, bins);
     }
     {
@@ -439,7 +589,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.tstride = f->tstride;
         ProfScope ps(f, kMemoRoute + off, s);
         hipLaunchKernelGGL(k_memo, dim3(f->m_pad / kMemoP, (unsigned)((max_rows + kMemoU - 1) / kMemoU)),
-                           dim3(kBlock), 0, s, m);
+                           dim3(kMemoBlock), memo_lds_bytes(f), s, m);
     }
     {
         TileArgs t{};
