@@ -198,7 +198,7 @@ struct MemoArgs {
     const int* tabR;
     const float *tabG, *tabS;
     float2* memo;
-    int n_inst, m_pad, tstride;
+    int n_inst, m_pad, tstride, lds_stride;
 };
 
 // (E, kappa) for kMemoU distinct lengths x kMemoP instances (consecutive
@@ -217,14 +217,15 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
     if (u0 >= U) return;
     const int p0 = blockIdx.x * kMemoP;
     const int tid = threadIdx.x, lane = lane_id(), pi = tid / kWave;
-    int* sR = reinterpret_cast<int*>(lds) + (size_t)pi * a.tstride;   // this wave's copy
+    // this wave's copy, 16 bits per length (lengths are below 32768)
+    uint16_t* sR = reinterpret_cast<uint16_t*>(lds) + (size_t)pi * a.lds_stride;
     constexpr int kPerLane = kMemoU / kWave;
     const int p = p0 + pi;
     const int g = p < a.n_inst ? a.order[p] : -1;
     if (g >= 0) {
         const int N = a.hN[g];
         const int* R = a.tabR + (size_t)g * a.tstride;
-        for (int k = lane; k <= N; k += kWave) sR[k] = R[k];
+        for (int k = lane; k <= N; k += kWave) sR[k] = (uint16_t)R[k];
         int Lv[kPerLane];
 #pragma unroll
         for (int i = 0; i < kPerLane; ++i) {
@@ -244,7 +245,7 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
             int lo = 0, hi = N;
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
-                if (sR[mid] <= Lv[i]) lo = mid; else hi = mid - 1;
+                if ((int)sR[mid] <= Lv[i]) lo = mid; else hi = mid - 1;
             }
             kk[i] = lo;
         }
@@ -450,7 +451,8 @@ __global__ __launch_bounds__(kBlock) void k_tile(TileArgs a)
     ReqRec rec;
     rec.c0 = 0.f; rec.D = -__builtin_inff(); rec.pex = -1; rec.orig = -1;
     if (lane < nreq) rec = a.recs[r0 + lane];
-    const float Dc = fminf(rec.D, FLT_MAX);   // padded positions hold +inf and must stay infeasible
+    // padded positions hold T = +inf and must stay infeasible even for D = +inf; a NaN budget is never met
+    const float Dc = rec.D > FLT_MAX ? FLT_MAX : rec.D;
     TileState st;
 #pragma unroll
     for (int j = 0; j < kTileReq; ++j) {
@@ -534,7 +536,9 @@ bool set_lds(K kernel, size_t bytes)
 
 }  // namespace
 
-size_t memo_lds_bytes(const gr_fleet* f) { return (size_t)kMemoP * f->tstride * 4; }
+int memo_lds_stride(const gr_fleet* f) { return (f->tstride + 1) & ~1; }
+
+size_t memo_lds_bytes(const gr_fleet* f) { return (size_t)kMemoP * memo_lds_stride(f) * 2; }
 
 size_t score_lds_bytes(const gr_fleet* f)
 {
@@ -586,7 +590,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         m.totals = f->totals; m.row_len = f->row_len; m.order = f->order; m.hN = f->hN; m.hQ = f->hQ;
         m.cls = f->cls; m.inst_class = f->inst_class;
         m.tabR = f->tabR; m.tabG = f->tabG; m.tabS = f->tabS; m.memo = f->memo;
-        m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.tstride = f->tstride;
+        m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.tstride = f->tstride; m.lds_stride = memo_lds_stride(f);
         ProfScope ps(f, kMemoRoute + off, s);
         hipLaunchKernelGGL(k_memo, dim3(f->m_pad / kMemoP, (unsigned)((max_rows + kMemoU - 1) / kMemoU)),
                            dim3(kMemoBlock), memo_lds_bytes(f), s, m);

@@ -1,0 +1,223 @@
+"""GPU parity on the degenerate and extreme inputs of the path, and the error
+behaviour of the C interface.  Custom fleets are plain namespaces with the
+array attributes of workloads.Fleet."""
+from types import SimpleNamespace
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_16867_amd import binding, workloads
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+CLASSES = [(2e-5, 0.012, 2e-4, 2e-8), (5e-5, 0.025, 4e-4, 5e-8), (1.2e-4, 0.05, 8e-4, 1e-7)]
+
+
+def fleet(inst_class, actives, queued, incoming, budgets, act_budget=None, refreshed=None,
+          classes=CLASSES, max_len=4096):
+    """actives: per instance arrays (prompt, gen, rem) as [n,3]; queued: [n,2]; incoming: [R,2]."""
+    i32 = lambda a: np.ascontiguousarray(a, dtype=np.int32)
+    A = [np.asarray(a, dtype=np.int64).reshape(-1, 3) for a in actives]
+    Q = [np.asarray(q, dtype=np.int64).reshape(-1, 2) for q in queued]
+    a = np.concatenate(A) if A else np.zeros((0, 3), np.int64)
+    q = np.concatenate(Q) if Q else np.zeros((0, 2), np.int64)
+    inc = np.asarray(incoming, dtype=np.int64).reshape(-1, 2)
+    names = ("delta", "alpha", "beta", "gamma")
+    na = len(a)
+    return SimpleNamespace(
+        coef={k: np.array([c[i] for c in classes], dtype=np.float64) for i, k in enumerate(names)},
+        inst_class=i32(inst_class), max_len=max_len,
+        act_off=i32(np.cumsum([0] + [len(x) for x in A])),
+        act_prompt=i32(a[:, 0]), act_gen=i32(a[:, 1]), act_rem=i32(a[:, 2]),
+        act_rem_refreshed=i32(a[:, 2] if refreshed is None else refreshed),
+        act_budget=np.ascontiguousarray(np.full(na, 1e9) if act_budget is None else act_budget,
+                                        dtype=np.float32),
+        q_off=i32(np.cumsum([0] + [len(x) for x in Q])),
+        q_prompt=i32(q[:, 0]), q_len=i32(q[:, 1]),
+        in_prompt=i32(inc[:, 0]), in_len=i32(inc[:, 1]),
+        in_budget=np.ascontiguousarray(budgets, dtype=np.float32))
+
+
+def rand_entries(rng, n, max_len=4096):
+    return np.stack([rng.integers(128, 2049, n), rng.integers(0, 201, n),
+                     np.clip(np.rint(rng.lognormal(5, 1, n)), 1, max_len)], axis=1)
+
+
+def solo(P, L, c=CLASSES[0]):
+    return c[0] * P + L * (c[1] + c[2]) + c[3] * (P * L + L * (L - 1) / 2)
+
+
+def test_empty_and_queue_only_instances():
+    rng = np.random.default_rng(0)
+    acts = [rand_entries(rng, 70), np.zeros((0, 3)), np.zeros((0, 3)), rand_entries(rng, 1),
+            rand_entries(rng, 300)]
+    queued = [[], [], [(500, 40), (900, 7)], [], [(128, 4096)]]
+    inc = np.stack([rng.integers(128, 2049, 500), np.clip(np.rint(rng.lognormal(5, 1, 500)), 1, 4096)], 1)
+    bud = rng.uniform(1.0, 8.0, 500) * solo(inc[:, 0], inc[:, 1])
+    fl = fleet([0, 1, 2, 0, 1], acts, queued, inc, bud)
+    sim = oracle.simulate(fl)
+    fl.act_budget = (sim.act_finish * rng.uniform(0.5, 1.5, len(sim.act_finish))).astype(np.float32)
+    rep = parity.run_and_check(fl)
+    assert rep["route_n"] == 500 and 0 < rep["flag_frac"] < 1
+
+
+def test_all_instances_empty():
+    inc = [(100, 1), (2048, 4096), (1, 1)]
+    fl = fleet([0, 1, 1, 2], [[], [], [], []], [[], [], [], []], inc,
+               [solo(100, 1), solo(2048, 4096) * 3, 0.0])
+    parity.run_and_check(fl)
+
+
+def test_identical_instances_tie_to_lowest_index():
+    rng = np.random.default_rng(1)
+    e = rand_entries(rng, 100)
+    inc = np.stack([rng.integers(128, 2049, 64), rng.integers(1, 2000, 64)], 1)
+    # huge budgets: all feasible, equal d_g -> instance 0; zero budgets: fallback, equal T -> instance 0
+    for scale in (1e6, 0.0):
+        fl = fleet([1, 1, 1, 1, 1, 1], [e] * 6, [[]] * 6, inc, scale * solo(inc[:, 0], inc[:, 1]))
+        parity.run_and_check(fl)
+    d = parity.upload(fl)
+    import torch
+    h = parity.make_handle(fl)
+    fin = torch.empty(len(fl.act_prompt), dtype=torch.float32, device="cuda:0")
+    h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"], d["q_off"],
+                      d["q_prompt"], d["q_len"], fin)
+    inst = torch.empty(64, dtype=torch.int32, device="cuda:0")
+    sl = torch.empty(64, dtype=torch.float32, device="cuda:0")
+    ex = torch.zeros(64, dtype=torch.int32, device="cuda:0")
+    h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, sl, exclude_inst=ex)
+    torch.cuda.synchronize()
+    assert (inst.cpu().numpy() == 1).all()       # instance 0 excluded: next lowest index
+    h.close()
+
+
+def test_single_instance_and_everything_excluded():
+    rng = np.random.default_rng(2)
+    inc = [(300, 50), (700, 10)]
+    fl = fleet([0], [rand_entries(rng, 10)], [[]], inc, [1e9, 0.0])
+    parity.run_and_check(fl)
+    rep = parity.run_and_check(fl, exclude=np.array([0, 0], dtype=np.int32))
+    assert rep["route_n"] == 2
+    # a risk scan on one instance has no other instance to go to: targets are -1
+    fl.act_budget = np.zeros(10, dtype=np.float32)
+    parity.run_and_check(fl)
+
+
+def test_exclusion_of_the_would_be_choice():
+    """Excluding exactly the instance Alg. 1 would have picked forces the second pass."""
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=2.0, seed=11))
+    sim = oracle.simulate(fl)
+    first = sim.route(fl.in_prompt, fl.in_len, fl.in_budget.astype(np.float64))
+    rep = parity.run_and_check(fl, exclude=first.inst)
+    assert 0.05 < rep["route_feasible_frac"] < 1.0
+
+
+def test_one_length_many_requests_and_all_lengths_distinct():
+    rng = np.random.default_rng(3)
+    acts = [rand_entries(rng, int(n)) for n in rng.integers(1, 400, 70)]
+    cls = rng.integers(0, 3, 70)
+    n = 5000
+    same = np.stack([rng.integers(128, 2049, n), np.full(n, 137)], 1)
+    fl = fleet(cls, acts, [[]] * 70, same, rng.uniform(0.5, 30, n) * solo(same[:, 0], same[:, 1]))
+    parity.run_and_check(fl)
+    distinct = np.stack([rng.integers(128, 2049, 4096), rng.permutation(4096) + 1], 1)
+    fl = fleet(cls, acts, [[]] * 70, distinct, rng.uniform(0.5, 30, 4096) * solo(distinct[:, 0], distinct[:, 1]))
+    parity.run_and_check(fl)
+
+
+def test_special_budgets():
+    rng = np.random.default_rng(4)
+    acts = [rand_entries(rng, 200) for _ in range(9)]
+    inc = np.stack([rng.integers(128, 2049, 8), rng.integers(1, 4097, 8)], 1)
+    bud = np.array([np.inf, -np.inf, -5.0, 0.0, np.nan, 3.4e38, 1e-30, 50.0], dtype=np.float32)
+    fl = fleet(rng.integers(0, 3, 9), acts, [[]] * 9, inc, bud)
+    fl.act_budget = rng.choice(np.array([np.inf, -np.inf, -1.0, 0.0, 1e3], dtype=np.float32), 1800)
+    # NaN budget: never feasible on either side; the classifier treats NaN like "nothing feasible"
+    parity.run_and_check(fl)
+
+
+def test_extreme_sizes():
+    """Longest allowed lengths, most entries per instance, long prompts."""
+    rng = np.random.default_rng(5)
+    L = 32767
+    big = np.stack([rng.integers(1, 32769, 2048), rng.integers(0, 201, 2048),
+                    rng.choice([1, 2, L - 1, L], 2048)], 1)
+    mid = np.stack([rng.integers(1, 32769, 2047), rng.integers(0, 201, 2047),
+                    rng.integers(1, L + 1, 2047)], 1)
+    inc = np.stack([rng.integers(1, 32769, 300), rng.choice([1, L, L - 1, 5000], 300)], 1)
+    fl = fleet([0, 2, 1], [big, mid, np.zeros((0, 3))], [[], [(32768, L)], []], inc,
+               rng.uniform(0.5, 3000, 300) * solo(inc[:, 0], inc[:, 1]), max_len=L)
+    sim = oracle.simulate(fl)
+    fl.act_budget = (sim.act_finish * rng.uniform(0.9, 1.1, len(sim.act_finish))).astype(np.float32)
+    rep = parity.run_and_check(fl)
+    assert rep["finish_rel_err"] < 1e-6
+
+
+def test_error_codes_and_contract_violations():
+    import torch
+    dev = "cuda:0"
+    co = [[1e-5], [0.01], [1e-4], [1e-8]]
+    with pytest.raises(binding.GoodRouteError) as e:
+        binding.Fleet(*co, [0], 4097, 4096, 10)
+    assert e.value.code == -2
+    with pytest.raises(binding.GoodRouteError) as e:
+        binding.Fleet(*co, [0], 16, 40000, 10)
+    assert e.value.code == -2
+    with pytest.raises(binding.GoodRouteError) as e:
+        binding.Fleet(*co, [1], 16, 100, 10)          # class id out of range
+    assert e.value.code == -1
+    with pytest.raises(binding.GoodRouteError) as e:
+        binding.Fleet([[-1e-5]], co[1], co[2], co[3], [0], 16, 100, 10)
+    assert e.value.code == -1
+
+    h = binding.Fleet(*co, [0, 0], 4, 100, 8)
+    i32 = lambda a: torch.tensor(a, dtype=torch.int32, device=dev)
+    f32 = lambda n: torch.zeros(n, dtype=torch.float32, device=dev)
+    req = (i32([10] * 8), i32([5] * 8), f32(8), torch.zeros(8, dtype=torch.int32, device=dev), f32(8))
+    with pytest.raises(binding.GoodRouteError) as e:
+        h.gr_score_route(*req)
+    assert e.value.code == -4                         # no status yet
+    # 3 actives on instance 0 and 5 on instance 1 (one too many), a length beyond max_len
+    off, z = i32([0, 3, 8]), i32([0, 0, 0])
+    fin = f32(8)
+    h.gr_build_status(off, i32([10] * 8), i32([0] * 8), i32([5, 500, 7, 1, 2, 3, 4, 9]),
+                      z, i32([]), i32([]), fin)
+    assert h.gr_device_status() == 3                  # length clamped + entries dropped, no fault
+    big = (i32([10] * 9), i32([5] * 9), f32(9), torch.zeros(9, dtype=torch.int32, device=dev), f32(9))
+    with pytest.raises(binding.GoodRouteError) as e:
+        h.gr_score_route(*big)
+    assert e.value.code == -2
+    h.gr_score_route(*req)
+    torch.cuda.synchronize()
+    h.close()
+    h.close()                                         # idempotent
+
+
+def test_zero_requests_and_zero_actives():
+    import torch
+    dev = "cuda:0"
+    h = binding.Fleet([1e-5], [0.01], [1e-4], [1e-8], [0, 0, 0], 8, 100, 8)
+    e32 = torch.zeros(0, dtype=torch.int32, device=dev)
+    ef = torch.zeros(0, dtype=torch.float32, device=dev)
+    eu = torch.zeros(0, dtype=torch.uint8, device=dev)
+    off = torch.zeros(4, dtype=torch.int32, device=dev)
+    d = torch.zeros(3, dtype=torch.float64, device=dev)
+    rk = torch.full((3,), -1, dtype=torch.int32, device=dev)
+    h.gr_build_status(off, e32, e32, e32, off, e32, e32, ef, None, d, rk)
+    h.gr_score_route(e32, e32, ef, e32, ef)
+    n = torch.full((1,), 7, dtype=torch.int32, device=dev)
+    h.gr_risk_scan(off, e32, e32, e32, off, e32, e32, ef, eu, ef, e32, ef, n)
+    torch.cuda.synchronize()
+    assert d.cpu().tolist() == [0.01] * 3 and rk.cpu().tolist() == [0, 1, 2] and n.item() == 0
+    inst = torch.full((2,), -9, dtype=torch.int32, device=dev)
+    sl = torch.zeros(2, dtype=torch.float32, device=dev)
+    h.gr_score_route(torch.tensor([7, 9], dtype=torch.int32, device=dev),
+                     torch.tensor([3, 100], dtype=torch.int32, device=dev),
+                     torch.tensor([1e9, 0.0], dtype=torch.float32, device=dev), inst, sl)
+    torch.cuda.synchronize()
+    assert inst.cpu().tolist() == [0, 0]
+    want = 1e9 - (1e-5 * 7 + 3 * (0.01 + 1e-4) + 1e-8 * (7 * 3 + 3))
+    assert abs(sl[0].item() - want) <= 1e-4 * 1e9
+    h.close()

@@ -46,3 +46,34 @@ def test_large_fleet_sampled():
 def test_large_fleet_loose_slo_sampled():
     fl = workloads.make_fleet(workloads.spec("large", slo_scale=4.0, occupancy_jitter=True, seed=2))
     report("large x4", parity.run_and_check(fl, sample=4096))
+
+
+def test_migrate_fleet_full_size_sampled():
+    """1 024 instances x 1 000 held requests, drifted lengths: flags of all 1 024 000
+    requests, targets of a sample."""
+    fl = workloads.make_fleet(workloads.spec("migrate"))
+    rep = parity.run_and_check(fl, sample=3000)
+    report("migrate", rep)
+    assert rep["flag_frac"] > 0.9
+
+
+def test_migrate_fleet_loose_slo():
+    fl = workloads.make_fleet(workloads.spec("migrate", slo_scale=8.0, n_incoming=20000, seed=4))
+    rep = parity.run_and_check(fl, sample=3000)
+    report("migrate x8", rep)
+    assert 0.05 < rep["flag_frac"] < 0.95 and rep["migrate_feasible_frac"] > 0.05
+
+
+def test_heavy_fleet_full_size_sampled():
+    """The benchmark's own configuration and launch shapes: 4 096 instances, 262 144
+    incoming, 2.1 M held requests; decisions of a sample against the reference."""
+    fl = workloads.make_fleet(workloads.spec("heavy"))
+    rep = parity.run_and_check(fl, sample=2048)
+    report("heavy", rep)
+
+
+def test_heavy_fleet_loose_slo():
+    fl = workloads.make_fleet(workloads.spec("heavy", slo_scale=16.0, n_incoming=65536, seed=9))
+    rep = parity.run_and_check(fl, sample=2048)
+    report("heavy x16", rep)
+    assert rep["route_feasible_frac"] > 0.3

@@ -55,15 +55,16 @@ def test_classifier_accepts_reference_and_rejects_wrong_answers():
     T = sim.pair_T(fl.in_prompt, fl.in_len)
     D = fl.in_budget.astype(np.float64)
     ref = sim.route(fl.in_prompt, fl.in_len, D)
-    want, robust, adm = parity.classify_choices(T, D, sim.rank, None, ref.inst.astype(np.int64))
+    want, robust, adm, fbk = parity.classify_choices(T, D, sim.rank, None, ref.inst.astype(np.int64))
     assert np.array_equal(want, ref.inst) and adm.all()
+    assert np.array_equal(fbk[fbk >= 0], ref.fallback[fbk >= 0]) and (fbk >= 0).mean() > 0.99
     assert robust.mean() > 0.99 and 0.1 < ref.fallback.mean() < 0.9
     wrong = (ref.inst.astype(np.int64) + 1) % fl.n_inst
-    _, _, adm2 = parity.classify_choices(T, D, sim.rank, None, wrong)
+    _, _, adm2, _ = parity.classify_choices(T, D, sim.rank, None, wrong)
     assert adm2[robust].mean() < 0.05
     # with an excluded instance the reference never returns it
     ex = ref.inst.copy()
     ref2 = sim.route(fl.in_prompt, fl.in_len, D, exclude=ex)
     assert np.all(ref2.inst != ex)
-    want2, _, adm3 = parity.classify_choices(T, D, sim.rank, ex, ref2.inst.astype(np.int64))
+    want2, _, adm3, _ = parity.classify_choices(T, D, sim.rank, ex, ref2.inst.astype(np.int64))
     assert np.array_equal(want2, ref2.inst) and adm3.all()
