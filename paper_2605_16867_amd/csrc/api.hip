@@ -81,7 +81,7 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
     f->ncap = ((max_entries_per_inst + kWave - 1) / kWave) * kWave;
     if (f->ncap == 0) f->ncap = kWave;
     f->tstride = max_entries_per_inst + 1;
-    f->m_pad = ((n_inst + kWave - 1) / kWave) * kWave;
+    f->m_pad = ((n_inst + 2 * kWave - 1) / (2 * kWave)) * (2 * kWave);
     f->bins = max_len + 1;
     f->row_cap = f->req_cap < f->bins ? f->req_cap : f->bins;
     if (f->row_cap < 1) f->row_cap = 1;
@@ -93,7 +93,7 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         dev_alloc(&f->cls, n_class) && dev_alloc(&f->inst_class, n_inst) &&
         dev_alloc(&f->tabR, tab) && dev_alloc(&f->tabG, tab) && dev_alloc(&f->tabS, tab) &&
         dev_alloc(&f->hN, n_inst) && dev_alloc(&f->hQ, n_inst) && dev_alloc(&f->hD, n_inst) &&
-        dev_alloc(&f->rank_acc, n_inst) && dev_alloc(&f->rank, n_inst) && dev_alloc(&f->order, f->m_pad) &&
+        dev_alloc(&f->rank_acc, n_inst) && dev_alloc(&f->rank, n_inst) && dev_alloc(&f->order, f->m_pad) && dev_alloc(&f->posK, f->m_pad) &&
         dev_alloc(&f->act_inst, f->max_active) && dev_alloc(&f->counters, 1) &&
         dev_alloc(&f->len_cnt, f->bins) && dev_alloc(&f->len_base, f->bins) &&
         dev_alloc(&f->row_len, f->row_cap) && dev_alloc(&f->row_off, f->row_cap + 1) &&
@@ -125,7 +125,7 @@ int gr_destroy(gr_fleet* f)
     if (!f) return GR_OK;
     (void)hipDeviceSynchronize();
     void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabG, f->tabS, f->hN, f->hQ, f->hD, f->rank_acc,
-                    f->rank, f->order, f->act_inst, f->counters, f->len_cnt, f->len_base, f->row_len,
+                    f->rank, f->order, f->posK, f->act_inst, f->counters, f->len_cnt, f->len_base, f->row_len,
                     f->row_off, f->tile_off, f->totals, f->recs, f->memo};
     int rc = GR_OK;
     for (void* p : ptrs)

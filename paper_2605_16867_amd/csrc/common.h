@@ -34,7 +34,7 @@ constexpr int kWaves = kBlock / kWave;
 constexpr int kMaxEntries = 2048;
 constexpr int kMaxClasses = 64;
 constexpr int kMaxLen = 32767;     // one LDS counter per length in the grouping kernels
-constexpr int kTileReq = 16;       // requests of one length scored together by one wave
+constexpr int kTileReq = 32;       // requests of one length scored together by one wave
 constexpr int kGroupItems = 16;    // requests per thread in the grouping kernels
 constexpr int kGroupChunk = kBlock * kGroupItems;
 constexpr int kMemoU = 256;        // lengths per workgroup of the memo kernel
@@ -94,7 +94,7 @@ struct gr_fleet {
     int idx_bits = 0, key_bits = 0;
     int ncap = 0;          // entries the sort buffers hold (multiple of 64)
     int tstride = 0;       // table entries per instance, max_entries + 1
-    int m_pad = 0;         // instances rounded up to a multiple of 64
+    int m_pad = 0;         // instances rounded up to a multiple of 128 (two blocks of 64 positions)
     int bins = 0;          // max_len + 1
     int64_t row_cap = 0;   // rows of the memo table
     int device = 0;
@@ -112,6 +112,7 @@ struct gr_fleet {
     int* rank_acc = nullptr; // [M] partial counts of the rank kernels
     int* rank = nullptr;     // [M]
     int* order = nullptr;    // [m_pad] order[rank[g]] = g
+    float2* posK = nullptr;  // [m_pad] (delta, gamma) of the instance at each position of the capability order
     int* act_inst = nullptr; // [max_active] instance of each active request
     int* counters = nullptr; // [1] GR_DEV_* bits
     // scoring workspace
@@ -122,7 +123,7 @@ struct gr_fleet {
     int* tile_off = nullptr;  // [row_cap+1] first tile of each distinct length
     int* totals = nullptr;    // [4] requests, distinct lengths, tiles
     gr::ReqRec* recs = nullptr;  // [req_cap] requests in grouped order
-    float2* memo = nullptr;      // [row_cap][m_pad] (E, kappa) per distinct length and position
+    float* memo = nullptr;       // [row_cap][m_pad] E per distinct length and position
 };
 
 namespace gr {

@@ -197,11 +197,11 @@ struct MemoArgs {
     const int* inst_class;
     const int* tabR;
     const float *tabG, *tabS;
-    float2* memo;
+    float* memo;
     int n_inst, m_pad, tstride, lds_stride;
 };
 
-// (E, kappa) for kMemoU distinct lengths x kMemoP instances (consecutive
+// E for kMemoU distinct lengths x kMemoP instances (consecutive
 // positions of the capability order) per workgroup of kMemoP waves.  A wave
 // takes one instance: it copies the instance's sorted lengths to LDS, its lanes
 // take the request lengths and find k = #{R_i <= L} by binary search there; the
@@ -211,7 +211,7 @@ constexpr int kMemoBlock = kMemoP * kWave;
 __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
 {
     extern __shared__ uint32_t lds[];
-    __shared__ float2 tile[kMemoU][kMemoP + 1];
+    __shared__ float tile[kMemoU][kMemoP + 1];
     const int U = a.totals[1];
     const int u0 = blockIdx.y * kMemoU;
     if (u0 >= U) return;
@@ -258,12 +258,12 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
             const double tri = Ld * (Ld - 1.0) * 0.5;
             const double E = q + cc.alpha * Ld + cc.beta * (n1 * Ld) + (double)Gv[i]
                              + cc.gamma * (Ld * (double)Sv[i] + n1 * tri);
-            tile[lane + kWave * i][pi] = make_float2((float)E, (float)(cc.delta + cc.gamma * Ld));
+            tile[lane + kWave * i][pi] = (float)E;
         }
     } else {
 #pragma unroll
         for (int i = 0; i < kPerLane; ++i)
-            tile[lane + kWave * i][pi] = make_float2(__builtin_inff(), 0.f);
+            tile[lane + kWave * i][pi] = __builtin_inff();
     }
     __syncthreads();
     const int col = tid % kMemoP;
@@ -277,9 +277,10 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
 
 // ------------------------------------------------------------------ Alg. 1 over tiles
 struct TileArgs {
-    const int *totals, *row_off, *tile_off, *order;
+    const int *totals, *row_len, *row_off, *tile_off, *order;
     const ReqRec* recs;
-    const float2* memo;
+    const float* memo;     // [row][m_pad] E of (distinct length, position in capability order)
+    const float2* posK;    // [m_pad] (delta, gamma) of the instance at each position
     int* out_inst;
     float* out_slack;
     uint8_t* out_fallback;
@@ -292,115 +293,168 @@ __device__ inline float readlane_f(float v, int lane)
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
-// One step of a wave-wide minimum: combine with the lane selected by a DPP control.
-template <int kCtrl, int kRowMask>
-__device__ inline float min_dpp(float v)
+// kappa = delta + gamma * L, the same instruction wherever a pair's latency is formed
+__device__ inline float kappa_of(float2 dg, float Lf) { return fmaf(dg.y, Lf, dg.x); }
+
+// Wave-wide minima of four registers at once (no NaNs among the inputs): on
+// return lane 63 of each holds the minimum over the 64 lanes.  Prefix minima
+// inside each row of 16 lanes (row_shr 1, 2, 4, 8), then lane 15 of rows 0 and
+// 2 into rows 1 and 3, then lane 31 into rows 2 and 3.  A lane without a
+// source keeps its value.  The four chains are interleaved so that a register
+// is read through DPP no sooner than three instructions after it was written
+// (the hardware asks for two); the leading s_nop covers whatever wrote the
+// inputs.
+__device__ inline void wave_min4(float& a, float& b, float& c, float& d)
 {
-    const int t = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), kCtrl, kRowMask, 0xf, false);
-    const float o = __int_as_float(t);
-    return o < v ? o : v;
+#define GR_MIN_STEP(ctrl)                          \
+    "v_min_f32_dpp %0, %0, %0 " ctrl "\n\t"        \
+    "v_min_f32_dpp %1, %1, %1 " ctrl "\n\t"        \
+    "v_min_f32_dpp %2, %2, %2 " ctrl "\n\t"        \
+    "v_min_f32_dpp %3, %3, %3 " ctrl "\n\t"
+    asm volatile("s_nop 1\n\t"
+                 GR_MIN_STEP("row_shr:1 row_mask:0xf bank_mask:0xf")
+                 GR_MIN_STEP("row_shr:2 row_mask:0xf bank_mask:0xf")
+                 GR_MIN_STEP("row_shr:4 row_mask:0xf bank_mask:0xf")
+                 GR_MIN_STEP("row_shr:8 row_mask:0xf bank_mask:0xf")
+                 GR_MIN_STEP("row_bcast:15 row_mask:0xa bank_mask:0xf")
+                 GR_MIN_STEP("row_bcast:31 row_mask:0xc bank_mask:0xf")
+                 "s_nop 1"
+                 : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+#undef GR_MIN_STEP
 }
 
-// Minimum over the 64 lanes (no NaNs among the inputs).  Prefix minima inside
-// each row of 16 lanes (row_shr 1, 2, 4, 8), then lane 15 of rows 0 and 2 into
-// rows 1 and 3, then lane 31 into rows 2 and 3: lane 63 holds the result.
 __device__ inline float wave_min(float v)
 {
-    v = min_dpp<0x111, 0xf>(v);
-    v = min_dpp<0x112, 0xf>(v);
-    v = min_dpp<0x114, 0xf>(v);
-    v = min_dpp<0x118, 0xf>(v);
-    v = min_dpp<0x142, 0xa>(v);
-    v = min_dpp<0x143, 0xc>(v);
+    float b = v, c = v, d = v;
+    wave_min4(v, b, c, d);
     return readlane_f(v, kWave - 1);
 }
 
-struct TileState {
-    float c0[kTileReq];     // same in every lane: tokens to prefill of request j (0 past the tile's last request)
-    float D[kTileReq];      // same in every lane: budget of request j; -inf once its instance is found
-    float minT[kTileReq];   // per lane: smallest T of request j over the blocks seen
-    int minB[kTileReq];     // per lane: the block it was seen in
-    unsigned notfound;      // bit j: request j has no feasible instance so far
-    int foundP;             // lane j: position of request j's first feasible instance
-    float foundT;           // lane j: its T
-};
-
-// Request j has feasible instances in block b (lanes `feas`): the first one in
-// capability order is its just-enough choice.
-__device__ inline void record_found(TileState& st, int j, int b, unsigned long long feas, float T, int lane)
+// Put a wave-uniform value into lane kLane of a vector register.
+template <int kLane>
+__device__ inline void writelane(float& dst, float uniform_value)
 {
-    const int fl = __ffsll((long long)feas) - 1;
-    const float Tf = readlane_f(T, fl);
-    if (lane == j) { st.foundP = b * kWave + fl; st.foundT = Tf; }
-    st.notfound &= ~(1u << j);
-    st.D[j] = -__builtin_inff();
+    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(uniform_value), "n"(kLane));
 }
 
-// One block of 64 instances against the tile's requests: per pair one
-// multiply-add, the feasibility compare and the running minimum (5 vector
-// operations).  Feasibility is only OR-ed here and looked at per request when
-// the block has any.
-__device__ inline void block_step(TileState& st, int b, float2 cur, int lane)
+template <int kLane>
+__device__ inline void writelane(int& dst, int uniform_value)
 {
-    unsigned long long anyf = 0;
-#pragma unroll
-    for (int j = 0; j < kTileReq; ++j) {
-        const float T = fmaf(st.c0[j], cur.y, cur.x);
-        anyf |= __ballot(T <= st.D[j]);
-        const bool lt = T < st.minT[j];
-        st.minB[j] = lt ? b : st.minB[j];
-        st.minT[j] = lt ? T : st.minT[j];
-    }
-    if (anyf) {
-        // rare: recomputed from opaque copies so that nothing of it stays live in the loop above
-        asm volatile("" : "+v"(cur.x), "+v"(cur.y));
-#pragma unroll
-        for (int j = 0; j < kTileReq; ++j) {
-            const float T = fmaf(st.c0[j], cur.y, cur.x);
-            const unsigned long long feas = __ballot(T <= st.D[j]);
+    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(uniform_value), "n"(kLane));
+}
+
+// Requests kJ0 .. kJ0+3 of a tile: their least latency over the wave and the
+// lane that holds it (kWave when several lanes do), left in lanes kJ0 .. kJ0+3
+// of Tm and win.
+template <int kJ0>
+__device__ inline void tile_minima4(const float (&minT)[kTileReq], float& Tm, int& win)
+{
+    float r0 = minT[kJ0], r1 = minT[kJ0 + 1], r2 = minT[kJ0 + 2], r3 = minT[kJ0 + 3];
+    wave_min4(r0, r1, r2, r3);
+    const float m0 = readlane_f(r0, kWave - 1), m1 = readlane_f(r1, kWave - 1),
+                m2 = readlane_f(r2, kWave - 1), m3 = readlane_f(r3, kWave - 1);
+    auto winner = [](unsigned long long cand) {
+        return (cand && !(cand & (cand - 1))) ? __ffsll((long long)cand) - 1 : kWave;
+    };
+    writelane<kJ0>(Tm, m0);
+    writelane<kJ0 + 1>(Tm, m1);
+    writelane<kJ0 + 2>(Tm, m2);
+    writelane<kJ0 + 3>(Tm, m3);
+    writelane<kJ0>(win, winner(__ballot(minT[kJ0] == m0)));
+    writelane<kJ0 + 1>(win, winner(__ballot(minT[kJ0 + 1] == m1)));
+    writelane<kJ0 + 2>(win, winner(__ballot(minT[kJ0 + 2] == m2)));
+    writelane<kJ0 + 3>(win, winner(__ballot(minT[kJ0 + 3] == m3)));
+}
+
+struct RowView {
+    const float* __restrict__ E;       // this length's row of the memo table
+    const float2* __restrict__ posK;
+    const int* __restrict__ order;
+    float Lf;
+    int nblk;                          // blocks of 64 positions (even)
+};
+
+// First feasible position in capability order for the few requests of a tile
+// that have one (bit j of `fm`): blocks in order, the requests still open one
+// after the other.  Exclusions are not applied here.
+__device__ inline void first_feasible_sparse(const RowView& rv, float rec_c0, float Dc, unsigned long long fm,
+                                             int lane, int& foundP, float& foundT)
+{
+    float En = rv.E[lane];
+    float2 Kn = rv.posK[lane];
+    for (int b = 0; b < rv.nblk && fm; ++b) {
+        const float e = En, k = kappa_of(Kn, rv.Lf);
+        if (b + 1 < rv.nblk) { En = rv.E[(b + 1) * kWave + lane]; Kn = rv.posK[(b + 1) * kWave + lane]; }
+        unsigned long long m = fm;
+        while (m) {
+            const int j = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const float T = fmaf(readlane_f(rec_c0, j), k, e);
+            const unsigned long long feas = __ballot(T <= readlane_f(Dc, j));
             if (feas) {
-                // the first feasible instance in capability order is the just-enough choice
                 const int fl = __ffsll((long long)feas) - 1;
                 const float Tf = readlane_f(T, fl);
-                if (lane == j) { st.foundP = b * kWave + fl; st.foundT = Tf; }
-                st.notfound &= ~(1u << j);
-                st.D[j] = -__builtin_inff();
+                if (lane == j) { foundP = b * kWave + fl; foundT = Tf; }
+                fm &= ~(1ull << j);
             }
         }
     }
 }
 
-// Smallest T of one request over the wave: position (ties to the lowest instance) and value.
-__device__ inline void wave_argmin(float minT, int minB, const int* __restrict__ order, int& pos, float& val)
+// The same when many requests of the tile have a feasible instance: all
+// requests against each block, two vector operations per pair; a request that
+// is done (or never had one) carries D = -inf.
+__device__ inline void first_feasible_dense(const RowView& rv, const float (&c0)[kTileReq], float Dc,
+                                            unsigned long long fm, int lane, int& foundP, float& foundT)
 {
-    const float Tm = wave_min(minT);
-    unsigned long long cand = __ballot(minT == Tm && Tm < __builtin_inff());
-    int bp = -1, bg = 0x7fffffff;
-    while (cand) {
-        const int l = __ffsll((long long)cand) - 1;
-        cand &= cand - 1;
-        const int p = __builtin_amdgcn_readlane(minB, l) * kWave + l;
-        const int g = order[p];
-        if (g < bg) { bg = g; bp = p; }
+    float D[kTileReq];
+#pragma unroll
+    for (int j = 0; j < kTileReq; ++j) {
+        D[j] = ((fm >> j) & 1ull) ? readlane_f(Dc, j) : -__builtin_inff();
+        asm volatile("" : "+v"(D[j]));     // 32 more scalars would not fit the scalar file
     }
-    pos = bp;
-    val = Tm;
+    unsigned left = (unsigned)fm;
+    float En = rv.E[lane];
+    float2 Kn = rv.posK[lane];
+    for (int b = 0; b < rv.nblk && left; ++b) {
+        float e = En, k = kappa_of(Kn, rv.Lf);
+        if (b + 1 < rv.nblk) { En = rv.E[(b + 1) * kWave + lane]; Kn = rv.posK[(b + 1) * kWave + lane]; }
+        unsigned long long any = 0;
+#pragma unroll
+        for (int j = 0; j < kTileReq; ++j) any |= __ballot(fmaf(c0[j], k, e) <= D[j]);
+        if (any) {
+            asm volatile("" : "+v"(e), "+v"(k));   // recomputed: nothing of this branch stays live above
+#pragma unroll
+            for (int j = 0; j < kTileReq; ++j) {
+                const float T = fmaf(c0[j], k, e);
+                const unsigned long long feas = __ballot(T <= D[j]);
+                if (feas) {
+                    const int fl = __ffsll((long long)feas) - 1;
+                    const float Tf = readlane_f(T, fl);
+                    if (lane == j) { foundP = b * kWave + fl; foundT = Tf; }
+                    left &= ~(1u << j);
+                    D[j] = -__builtin_inff();
+                }
+            }
+        }
+    }
 }
 
-// One request on its own against all instances but the one at position `pex`:
-// used when the choice made without the exclusion fell on the excluded instance.
-__device__ inline void rescan_excluding(const float2* __restrict__ row, int nblk, float c0, float D, int pex,
-                                        const int* __restrict__ order, int lane, int& pos, float& val, bool& found)
+// Alg. 1 for one request on its own, exactly: every position but `pex`, the
+// first feasible one in capability order, else the smallest T with ties to the
+// lowest instance index.  The rare cases of the tile pass end here: a choice
+// that fell on the excluded instance, equal minima.
+__device__ inline void exact_choice(const RowView& rv, float c0, float D, int pex, int lane,
+                                    int& pos, float& val, bool& found)
 {
     float minT = __builtin_inff();
-    int minB = 0;
+    int minP = -1, minG = 0x7fffffff;
     found = false;
-    pos = -1;
-    val = 0.f;
-    for (int b = 0; b < nblk; ++b) {
-        const float2 cur = row[b * kWave + lane];
-        float T = fmaf(c0, cur.y, cur.x);
-        if (b * kWave + lane == pex) T = __builtin_inff();
+    for (int b = 0; b < rv.nblk; ++b) {
+        const int p = b * kWave + lane;
+        const int g = rv.order[p];
+        float T = fmaf(c0, kappa_of(rv.posK[p], rv.Lf), rv.E[p]);
+        if (p == pex || g < 0) T = __builtin_inff();
         const unsigned long long feas = __ballot(T <= D);
         if (feas) {
             const int fl = __ffsll((long long)feas) - 1;
@@ -409,25 +463,45 @@ __device__ inline void rescan_excluding(const float2* __restrict__ row, int nblk
             found = true;
             return;
         }
-        const bool lt = T < minT;
-        minB = lt ? b : minB;
-        minT = lt ? T : minT;
+        if (T < minT || (T == minT && g >= 0 && g < minG)) { minT = T; minP = p; minG = g; }
     }
-    wave_argmin(minT, minB, order, pos, val);
+    const float Tm = wave_min(minT);
+    unsigned long long cand = __ballot(minT == Tm && Tm < __builtin_inff());
+    int bp = -1, bg = 0x7fffffff;
+    while (cand) {
+        const int l = __ffsll((long long)cand) - 1;
+        cand &= cand - 1;
+        const int g = __builtin_amdgcn_readlane(minG, l);
+        if (g < bg) { bg = g; bp = __builtin_amdgcn_readlane(minP, l); }
+    }
+    pos = bp;
+    val = bp >= 0 ? Tm : 0.f;
 }
 
+constexpr int kSparseFeasible = 8;   // up to this many feasible requests of a tile go one by one
+
 // One wave per tile: up to kTileReq requests of one length against all
-// instances, 64 instances (one block of the capability order) per step.
-// Excluded instances are ignored in the main pass; a request whose choice
-// falls on its excluded instance is scored again on its own.
+// instances.  Lane = position in capability order within a block of 64; the
+// requests' prefill lengths are wave-uniform scalars.
+//
+// Main pass, per pair: T = E + c0 * kappa (one multiply-add) folded into the
+// request's running minimum per lane (one three-way minimum per two pairs).
+// Alg. 1's feasible set is non-empty exactly when that minimum is <= D, so the
+// feasibility test of every pair is implied; only requests that have a
+// feasible instance are walked again, in capability order, up to their first
+// one (the just-enough choice).  The others take the instance of the minimum,
+// found by recomputing the positions of the lane that holds it (the earliest
+// position in capability order among equal minima).
 template <bool kWriteT>
-__global__ __launch_bounds__(kBlock) void k_tile(TileArgs a)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tile(TileArgs a)
 {
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int NT = a.totals[2], U = a.totals[1];
-    // consecutive tiles share a table row: keep them on one XCD (workgroups go round-robin over 8)
-    const int per_xcd = gridDim.x >> 3;
+    // consecutive tiles share a table row: keep them on one XCD (workgroups go round-robin over
+    // 8), each XCD taking an equal run of the workgroups that have tiles at all
+    const int per_xcd = ((NT + kWaves - 1) / kWaves + 7) >> 3;
+    if ((int)(blockIdx.x >> 3) >= per_xcd) return;
     const int bid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     const int t = bid * kWaves + wave;
     if (t >= NT) return;
@@ -450,62 +524,105 @@ __global__ __launch_bounds__(kBlock) void k_tile(TileArgs a)
     // lanes past the tile's last request carry a dummy that is never feasible and never reported
     ReqRec rec;
     rec.c0 = 0.f; rec.D = -__builtin_inff(); rec.pex = -1; rec.orig = -1;
-    if (lane < nreq) rec = a.recs[r0 + lane];
+    const bool mine = lane < nreq;
+    if (mine) rec = a.recs[r0 + lane];
     // padded positions hold T = +inf and must stay infeasible even for D = +inf; a NaN budget is never met
     const float Dc = rec.D > FLT_MAX ? FLT_MAX : rec.D;
-    TileState st;
+
+    RowView rv;
+    rv.E = a.memo + (size_t)u * a.m_pad;
+    rv.posK = a.posK;
+    rv.order = a.order;
+    rv.Lf = (float)a.row_len[u];
+    rv.nblk = a.m_pad / kWave;
+
+    float c0[kTileReq], minT[kTileReq];
 #pragma unroll
     for (int j = 0; j < kTileReq; ++j) {
-        st.c0[j] = readlane_f(rec.c0, j);
-        st.D[j] = readlane_f(Dc, j);
-        // keep both in vector registers: the scalar file is too small for 16 requests
-        asm volatile("" : "+v"(st.c0[j]), "+v"(st.D[j]));
-        st.minT[j] = __builtin_inff();
-        st.minB[j] = 0;
-    }
-    st.notfound = (1u << nreq) - 1u;
-    st.foundP = -1;
-    st.foundT = 0.f;
-
-    const float2* __restrict__ row = a.memo + (size_t)u * a.m_pad;
-    const int nblk = a.m_pad / kWave;
-    float2 next = row[lane];
-    for (int b = 0; b < nblk; ++b) {
-        const float2 cur = next;
-        if (b + 1 < nblk) next = row[(b + 1) * kWave + lane];
-        block_step(st, b, cur, lane);
+        c0[j] = readlane_f(rec.c0, j);
+        minT[j] = __builtin_inff();
     }
 
-    // requests with no feasible instance fall back to the smallest T
-    int bestP = -1;
-    float bestT = 0.f;
+    // ---- main pass: two blocks of 64 positions per step
+    {
+        float Ea = rv.E[lane], Eb = rv.E[kWave + lane];
+        float2 Ka = rv.posK[lane], Kb = rv.posK[kWave + lane];
+        for (int b = 0; b < rv.nblk; b += 2) {
+            const float ea = Ea, eb = Eb;
+            const float ka = kappa_of(Ka, rv.Lf), kb = kappa_of(Kb, rv.Lf);
+            if (b + 2 < rv.nblk) {
+                Ea = rv.E[(b + 2) * kWave + lane]; Eb = rv.E[(b + 3) * kWave + lane];
+                Ka = rv.posK[(b + 2) * kWave + lane]; Kb = rv.posK[(b + 3) * kWave + lane];
+            }
 #pragma unroll
-    for (int j = 0; j < kTileReq; ++j) {
-        if ((st.notfound >> j) & 1u) {
-            int bp;
-            float bt;
-            wave_argmin(st.minT[j], st.minB[j], a.order, bp, bt);
-            if (lane == j) { bestP = bp; bestT = bt; }
+            for (int j = 0; j < kTileReq; ++j) {
+                const float Ta = fmaf(c0[j], ka, ea), Tb = fmaf(c0[j], kb, eb);
+                minT[j] = fminf(fminf(minT[j], Ta), Tb);
+            }
         }
     }
-    bool found = !((st.notfound >> lane) & 1u);
-    int p = found ? st.foundP : bestP;
-    float T = found ? st.foundT : bestT;
 
-    // choices that fell on the request's excluded instance
-    unsigned long long redo = __ballot(lane < nreq && rec.pex >= 0 && p == rec.pex);
+    // ---- per request: the least latency and the lane that holds it (lane j keeps request j's)
+    float Tm = __builtin_inff();
+    int win = kWave;                 // lane holding the minimum; kWave when several do
+    static_assert(kTileReq == 32, "eight groups of four requests");
+    tile_minima4<0>(minT, Tm, win);
+    tile_minima4<4>(minT, Tm, win);
+    tile_minima4<8>(minT, Tm, win);
+    tile_minima4<12>(minT, Tm, win);
+    tile_minima4<16>(minT, Tm, win);
+    tile_minima4<20>(minT, Tm, win);
+    tile_minima4<24>(minT, Tm, win);
+    tile_minima4<28>(minT, Tm, win);
+
+    // ---- requests with a feasible instance: the first one in capability order
+    int foundP = -1;
+    float foundT = 0.f;
+    const unsigned long long fm = __ballot(mine && Tm <= Dc);
+    if (fm) {
+        if (__popcll(fm) <= kSparseFeasible) first_feasible_sparse(rv, rec.c0, Dc, fm, lane, foundP, foundT);
+        else first_feasible_dense(rv, c0, Dc, fm, lane, foundP, foundT);
+    }
+
+    // ---- the others: which of the winning lane's positions has T = the minimum.  Lane l looks
+    // for request l mod 32 in the blocks of parity l / 32; the earliest block wins.
+    const int src = lane & (kTileReq - 1);
+    const float s_c0 = __shfl(rec.c0, src, kWave), s_Tm = __shfl(Tm, src, kWave);
+    const int s_win = __shfl(win, src, kWave);
+    int firstB = 0x7fffffff;
+    if (__ballot(mine && foundP < 0)) {
+        const int lw = s_win & (kWave - 1);
+        const float* __restrict__ pe = rv.E + lw;
+        const float2* __restrict__ pk = rv.posK + lw;
+#pragma unroll 4
+        for (int b = lane >> 5; b < rv.nblk; b += 2) {
+            const float Tc = fmaf(s_c0, kappa_of(pk[b * kWave], rv.Lf), pe[b * kWave]);
+            if (Tc == s_Tm) firstB = min(firstB, b);
+        }
+    }
+    firstB = min(firstB, __shfl_xor(firstB, 32, kWave));
+    const int candP = firstB < rv.nblk ? firstB * kWave + (win & (kWave - 1)) : -1;
+    // equal minima in several lanes and a minimum on the excluded instance: one by one
+    const bool slow = mine && (foundP >= 0 ? foundP == rec.pex
+                                           : (win == kWave || candP < 0 || candP == rec.pex));
+
+    int p = foundP >= 0 ? foundP : candP;
+    float T = foundP >= 0 ? foundT : Tm;
+    bool found = foundP >= 0;
+
+    unsigned long long redo = __ballot(slow);
     while (redo) {
         const int j = __ffsll((long long)redo) - 1;
         redo &= redo - 1;
         int rp;
         float rt;
         bool rf;
-        rescan_excluding(row, nblk, readlane_f(rec.c0, j), readlane_f(Dc, j),
-                         __builtin_amdgcn_readlane(rec.pex, j), a.order, lane, rp, rt, rf);
+        exact_choice(rv, readlane_f(rec.c0, j), readlane_f(Dc, j), __builtin_amdgcn_readlane(rec.pex, j),
+                     lane, rp, rt, rf);
         if (lane == j) { p = rp; T = rt; found = rf; }
     }
 
-    if (lane < nreq) {
+    if (mine) {
         const int g = p >= 0 ? a.order[p] : -1;
         a.out_inst[rec.orig] = g;
         a.out_slack[rec.orig] = g >= 0 ? rec.D - T : 0.f;
@@ -513,12 +630,12 @@ __global__ __launch_bounds__(kBlock) void k_tile(TileArgs a)
     }
 
     if (kWriteT) {   // every pair's latency, for checking: same arithmetic, exclusions not applied
-        for (int b = 0; b < nblk; ++b) {
-            const float2 cur = row[b * kWave + lane];
+        for (int b = 0; b < rv.nblk; ++b) {
+            const float e = rv.E[b * kWave + lane], k = kappa_of(rv.posK[b * kWave + lane], rv.Lf);
             const int g_lane = a.order[b * kWave + lane];
             for (int j = 0; j < nreq; ++j) {
                 const int orig = __builtin_amdgcn_readlane(rec.orig, j);
-                const float Tj = fmaf(readlane_f(rec.c0, j), cur.y, cur.x);
+                const float Tj = fmaf(readlane_f(rec.c0, j), k, e);
                 if (g_lane >= 0) a.out_T[(size_t)orig * a.n_inst + g_lane] = Tj;
             }
         }
@@ -543,7 +660,7 @@ size_t memo_lds_bytes(const gr_fleet* f) { return (size_t)kMemoP * memo_lds_stri
 size_t score_lds_bytes(const gr_fleet* f)
 {
     const size_t group = (size_t)f->bins * 4;
-    const size_t memo = memo_lds_bytes(f) + sizeof(float2) * kMemoU * (kMemoP + 1);
+    const size_t memo = memo_lds_bytes(f) + sizeof(float) * kMemoU * (kMemoP + 1);
     return group > memo ? group : memo;
 }
 
@@ -597,8 +714,8 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     }
     {
         TileArgs t{};
-        t.totals = f->totals; t.row_off = f->row_off; t.tile_off = f->tile_off; t.order = f->order;
-        t.recs = f->recs; t.memo = f->memo;
+        t.totals = f->totals; t.row_len = f->row_len; t.row_off = f->row_off; t.tile_off = f->tile_off;
+        t.order = f->order; t.recs = f->recs; t.memo = f->memo; t.posK = f->posK;
         t.out_inst = out.inst; t.out_slack = out.slack; t.out_fallback = out.fallback; t.out_T = out.T;
         t.n_inst = f->n_inst; t.m_pad = f->m_pad;
         const int64_t max_tiles = (n + kTileReq - 1) / kTileReq + max_rows;

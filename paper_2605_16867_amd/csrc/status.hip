@@ -233,17 +233,22 @@ __global__ __launch_bounds__(kBlock) void k_rank_count(const double* __restrict_
 }
 
 __global__ __launch_bounds__(kBlock) void k_rank_final(const int* __restrict__ rank_acc, int n_inst, int m_pad,
+                                                       const ClassCoef* __restrict__ cls,
+                                                       const int* __restrict__ inst_class,
                                                        int* __restrict__ rank, int* __restrict__ order,
-                                                       int* __restrict__ out_rank)
+                                                       float2* __restrict__ posK, int* __restrict__ out_rank)
 {
     const int g = blockIdx.x * kBlock + threadIdx.x;
     if (g < n_inst) {
         const int r = rank_acc[g];
+        const ClassCoef cc = cls[inst_class[g]];
         rank[g] = r;
         order[r] = g;
+        posK[r] = make_float2((float)cc.delta, (float)cc.gamma);
         if (out_rank) out_rank[g] = r;
     } else if (g < m_pad) {
         order[g] = -1;     // positions past the last instance
+        posK[g] = make_float2(0.f, 0.f);
     }
 }
 
@@ -286,7 +291,8 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
     {
         ProfScope ps(f, kRankFinal, s);
         hipLaunchKernelGGL(k_rank_final, dim3((f->m_pad + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
-                           f->rank_acc, M, f->m_pad, f->rank, f->order, in.out_rank);
+                           f->rank_acc, M, f->m_pad, f->cls, f->inst_class, f->rank, f->order, f->posK,
+                           in.out_rank);
     }
     if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
     f->has_status = true;
