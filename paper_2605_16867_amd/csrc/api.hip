@@ -13,13 +13,6 @@ const char* const kKernelNames[kNumKernels] = {
     "k_hist<route>", "k_scan<route>", "k_scatter<route>", "k_memo<route>", "k_tile<route>",
     "k_hist<migrate>", "k_scan<migrate>", "k_scatter<migrate>", "k_memo<migrate>", "k_tile<migrate>"};
 
-int bits_for(int64_t v)
-{
-    int b = 0;
-    while ((int64_t(1) << b) <= v) ++b;
-    return b;
-}
-
 template <typename T>
 bool dev_alloc(T** p, size_t n)
 {
@@ -66,9 +59,6 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
             return GR_ERR_INVALID_ARG;
     for (int g = 0; g < n_inst; ++g)
         if (inst_class[g] < 0 || inst_class[g] >= n_class) return GR_ERR_INVALID_ARG;
-    const int idx_bits = bits_for(max_entries_per_inst > 0 ? max_entries_per_inst - 1 : 0);
-    const int key_bits = bits_for(max_len);
-    if (idx_bits + key_bits > 32) return GR_ERR_TOO_LARGE;
     if ((int64_t)n_inst * max_entries_per_inst > (int64_t(1) << 30)) return GR_ERR_TOO_LARGE;
 
     gr_fleet* f = new (std::nothrow) gr_fleet;
@@ -77,22 +67,21 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
     f->max_entries = max_entries_per_inst; f->max_len = max_len; f->max_requests = max_requests;
     f->max_active = (int64_t)n_inst * max_entries_per_inst;
     f->req_cap = f->max_active > max_requests ? f->max_active : max_requests;
-    f->idx_bits = idx_bits > 0 ? idx_bits : 1; f->key_bits = key_bits;
-    f->ncap = ((max_entries_per_inst + kWave - 1) / kWave) * kWave;
-    if (f->ncap == 0) f->ncap = kWave;
-    f->tstride = max_entries_per_inst + 1;
+    f->epl = 1;
+    while (kWave * f->epl < max_entries_per_inst) f->epl *= 2;
+    f->cap = kWave * f->epl;
     f->m_pad = ((n_inst + 2 * kWave - 1) / (2 * kWave)) * (2 * kWave);
     f->bins = max_len + 1;
     f->row_cap = f->req_cap < f->bins ? f->req_cap : f->bins;
     if (f->row_cap < 1) f->row_cap = 1;
     if (hipGetDevice(&f->device) != hipSuccess) { delete f; return GR_ERR_HIP; }
-    if (status_lds_bytes(f) > 160 * 1024 || score_lds_bytes(f) > 160 * 1024) { delete f; return GR_ERR_TOO_LARGE; }
+    if (score_lds_bytes(f) > 160 * 1024) { delete f; return GR_ERR_TOO_LARGE; }
 
-    const size_t tab = (size_t)n_inst * f->tstride;
+    const size_t tab = (size_t)n_inst * f->cap;
     const bool ok =
         dev_alloc(&f->cls, n_class) && dev_alloc(&f->inst_class, n_inst) &&
-        dev_alloc(&f->tabR, tab) && dev_alloc(&f->tabG, tab) && dev_alloc(&f->tabS, tab) &&
-        dev_alloc(&f->hN, n_inst) && dev_alloc(&f->hQ, n_inst) && dev_alloc(&f->hD, n_inst) &&
+        dev_alloc(&f->tabR, tab) && dev_alloc(&f->tabGH, tab) && dev_alloc(&f->headGH, n_inst) &&
+        dev_alloc(&f->hN, n_inst) && dev_alloc(&f->hD, n_inst) &&
         dev_alloc(&f->rank_acc, n_inst) && dev_alloc(&f->rank, n_inst) && dev_alloc(&f->order, f->m_pad) && dev_alloc(&f->posK, f->m_pad) &&
         dev_alloc(&f->act_inst, f->max_active) && dev_alloc(&f->counters, 1) &&
         dev_alloc(&f->len_cnt, f->bins) && dev_alloc(&f->len_base, f->bins) &&
@@ -115,7 +104,7 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         gr_destroy(f);
         return GR_ERR_HIP;
     }
-    if (status_prepare(f) != GR_OK || score_prepare(f) != GR_OK) { gr_destroy(f); return GR_ERR_HIP; }
+    if (score_prepare(f) != GR_OK) { gr_destroy(f); return GR_ERR_HIP; }
     *out = f;
     return GR_OK;
 }
@@ -124,7 +113,7 @@ int gr_destroy(gr_fleet* f)
 {
     if (!f) return GR_OK;
     (void)hipDeviceSynchronize();
-    void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabG, f->tabS, f->hN, f->hQ, f->hD, f->rank_acc,
+    void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabGH, f->headGH, f->hN, f->hD, f->rank_acc,
                     f->rank, f->order, f->posK, f->act_inst, f->counters, f->len_cnt, f->len_base, f->row_len,
                     f->row_off, f->tile_off, f->totals, f->recs, f->memo};
     int rc = GR_OK;

@@ -16,6 +16,8 @@
 //            = E_g(L) + c0 * kappa_g(L),
 //     E_g(L)     = q_g + W_g(L) + beta*L + gamma*tri(L)      (instance and length only)
 //     kappa_g(L) = delta + gamma*L.
+// On the segment R_k <= L < R_{k+1}, with n = N - k requests still running:
+//     E_g(L) = [q_g + beta*Y_k + gamma*X_k] + L*[alpha + beta*(n+1) + gamma*S_{k+1}] + tri(L)*gamma*(n+1).
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -37,8 +39,8 @@ constexpr int kMaxLen = 32767;     // one LDS counter per length in the grouping
 constexpr int kTileReq = 32;       // requests of one length scored together by one wave
 constexpr int kGroupItems = 16;    // requests per thread in the grouping kernels
 constexpr int kGroupChunk = kBlock * kGroupItems;
-constexpr int kMemoU = 256;        // lengths per workgroup of the memo kernel
-constexpr int kMemoP = 16;         // instances per workgroup of the memo kernel
+constexpr int kMemoU = 256;        // lengths per pass of a workgroup of the memo kernel
+constexpr int kMemoP = 16;         // instances (waves) per workgroup of the memo kernel
 
 struct ClassCoef {
     double delta, alpha, beta, gamma;
@@ -91,9 +93,8 @@ struct gr_fleet {
     int64_t max_requests = 0;
     int64_t max_active = 0;
     int64_t req_cap = 0;   // requests one scoring pass may hold
-    int idx_bits = 0, key_bits = 0;
-    int ncap = 0;          // entries the sort buffers hold (multiple of 64)
-    int tstride = 0;       // table entries per instance, max_entries + 1
+    int epl = 0;           // sort words per lane of the status build: 1, 2, 4 .. 32
+    int cap = 0;           // 64 * epl >= max_entries: table entries per instance
     int m_pad = 0;         // instances rounded up to a multiple of 128 (two blocks of 64 positions)
     int bins = 0;          // max_len + 1
     int64_t row_cap = 0;   // rows of the memo table
@@ -103,11 +104,11 @@ struct gr_fleet {
     gr::ClassCoef* cls = nullptr;
     int* inst_class = nullptr;
     // per-instance tables written by the status build
-    int* tabR = nullptr;     // [M][tstride] sorted remaining lengths, entry 0 = 0
-    float* tabG = nullptr;   // [M][tstride] beta*Y_k + gamma*X_k
-    float* tabS = nullptr;   // [M][tstride] S_{k+1}
+    // E_g(L) = Gq + L*H + tri(L)*gamma*(n+1) on the segment after the k shortest requests (n still running)
+    uint16_t* tabR = nullptr; // [M][cap] remaining lengths, ascending; 0xFFFF past the last entry
+    float2* tabGH = nullptr;  // [M][cap] (Gq, H) of segment k = index + 1
+    float2* headGH = nullptr; // [M] (Gq, H) of segment 0: (q_g, alpha + beta*(N+1) + gamma*sum of contexts)
     int* hN = nullptr;       // [M] entries per instance
-    double* hQ = nullptr;    // [M] q_g
     double* hD = nullptr;    // [M] d_g
     int* rank_acc = nullptr; // [M] partial counts of the rank kernels
     int* rank = nullptr;     // [M]
@@ -158,8 +159,6 @@ struct StatusIn {
 };
 
 // status.hip
-size_t status_lds_bytes(const gr_fleet* f);
-int status_prepare(gr_fleet* f);   // one-time kernel attributes
 int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s);
 
 // score.hip

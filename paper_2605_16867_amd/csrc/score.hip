@@ -192,86 +192,96 @@ __global__ __launch_bounds__(kBlock) void k_scatter(ReqSrc s, int* __restrict__ 
 // ------------------------------------------------------------------ closed-form lookups
 struct MemoArgs {
     const int *totals, *row_len, *order, *hN;
-    const double* hQ;
     const ClassCoef* cls;
     const int* inst_class;
-    const int* tabR;
-    const float *tabG, *tabS;
+    const uint16_t* tabR;
+    const float2 *tabGH, *headGH;
     float* memo;
-    int n_inst, m_pad, tstride, lds_stride;
+    int n_inst, m_pad, cap;
 };
 
-// E for kMemoU distinct lengths x kMemoP instances (consecutive
-// positions of the capability order) per workgroup of kMemoP waves.  A wave
-// takes one instance: it copies the instance's sorted lengths to LDS, its lanes
-// take the request lengths and find k = #{R_i <= L} by binary search there; the
-// tile is turned in LDS so that the table is written in rows of positions.
+// E of every (distinct length, instance).  A workgroup of kMemoP waves takes
+// kMemoP consecutive positions of the capability order, one instance per wave:
+// the wave copies the instance's sorted lengths (and, with kStage, its segment
+// coefficients) to LDS once, then walks the distinct lengths kMemoU at a time;
+// a lane takes a length, finds its segment k = #{R_i <= L} by binary search in
+// LDS and evaluates the segment's quadratic.  Each pass is turned in LDS so
+// that the table is written in runs of kMemoP positions per length.
 constexpr int kMemoBlock = kMemoP * kWave;
+constexpr int kMemoTile = kMemoU * (kMemoP + 1);       // floats
 
+template <bool kStage>
 __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
 {
     extern __shared__ uint32_t lds[];
-    __shared__ float tile[kMemoU][kMemoP + 1];
+    float* tile = reinterpret_cast<float*>(lds);
     const int U = a.totals[1];
-    const int u0 = blockIdx.y * kMemoU;
-    if (u0 >= U) return;
     const int p0 = blockIdx.x * kMemoP;
     const int tid = threadIdx.x, lane = lane_id(), pi = tid / kWave;
-    // this wave's copy, 16 bits per length (lengths are below 32768)
-    uint16_t* sR = reinterpret_cast<uint16_t*>(lds) + (size_t)pi * a.lds_stride;
+    uint16_t* sR = reinterpret_cast<uint16_t*>(tile + kMemoTile) + (size_t)pi * a.cap;
+    float2* sGH = reinterpret_cast<float2*>(reinterpret_cast<uint16_t*>(tile + kMemoTile) + (size_t)kMemoP * a.cap)
+                  + (size_t)pi * a.cap;
     constexpr int kPerLane = kMemoU / kWave;
     const int p = p0 + pi;
     const int g = p < a.n_inst ? a.order[p] : -1;
+    int N = 0;
+    float2 head = make_float2(0.f, 0.f);
+    float gam = 0.f;
+    const float2* GH = a.tabGH;
     if (g >= 0) {
-        const int N = a.hN[g];
-        const int* R = a.tabR + (size_t)g * a.tstride;
-        for (int k = lane; k <= N; k += kWave) sR[k] = (uint16_t)R[k];
-        int Lv[kPerLane];
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const int u = u0 + lane + kWave * i;
-            Lv[i] = u < U ? a.row_len[u] : 0;
+        N = a.hN[g];
+        head = a.headGH[g];
+        gam = (float)a.cls[a.inst_class[g]].gamma;
+        GH = a.tabGH + (size_t)g * a.cap;
+        const uint4* srcR = reinterpret_cast<const uint4*>(a.tabR + (size_t)g * a.cap);
+        for (int c = lane; c * 8 < N; c += kWave) reinterpret_cast<uint4*>(sR)[c] = srcR[c];
+        if (kStage) {
+            const float4* srcG = reinterpret_cast<const float4*>(GH);
+            for (int c = lane; c * 2 < N; c += kWave) reinterpret_cast<float4*>(sGH)[c] = srcG[c];
         }
-        const double q = a.hQ[g];
-        const ClassCoef cc = a.cls[a.inst_class[g]];
-        const float* G = a.tabG + (size_t)g * a.tstride;
-        const float* S = a.tabS + (size_t)g * a.tstride;
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        int kk[kPerLane];
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            int lo = 0, hi = N;
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if ((int)sR[mid] <= Lv[i]) lo = mid; else hi = mid - 1;
-            }
-            kk[i] = lo;
-        }
-        float Gv[kPerLane], Sv[kPerLane];
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i) { Gv[i] = G[kk[i]]; Sv[i] = S[kk[i]]; }
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i) {
-            const double Ld = (double)Lv[i], n1 = (double)(N - kk[i] + 1);
-            const double tri = Ld * (Ld - 1.0) * 0.5;
-            const double E = q + cc.alpha * Ld + cc.beta * (n1 * Ld) + (double)Gv[i]
-                             + cc.gamma * (Ld * (double)Sv[i] + n1 * tri);
-            tile[lane + kWave * i][pi] = (float)E;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < kPerLane; ++i)
-            tile[lane + kWave * i][pi] = __builtin_inff();
     }
-    __syncthreads();
-    const int col = tid % kMemoP;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    for (int u0 = blockIdx.y * kMemoU; u0 < U; u0 += gridDim.y * kMemoU) {
+        if (g >= 0) {
+            int Lv[kPerLane], kk[kPerLane];
 #pragma unroll
-    for (int it = 0; it < kMemoU * kMemoP / kMemoBlock; ++it) {
-        const int ul = tid / kMemoP + (kMemoBlock / kMemoP) * it;
-        const int u = u0 + ul;
-        if (u < U) a.memo[(size_t)u * a.m_pad + p0 + col] = tile[ul][col];
+            for (int i = 0; i < kPerLane; ++i) {
+                const int u = u0 + lane + kWave * i;
+                Lv[i] = u < U ? a.row_len[u] : 0;
+                kk[i] = 0;
+            }
+            // largest k <= N with R_k <= L (R_1 <= R_2 <= ..), the same number of probes for every lane
+            for (int step = a.cap; step >= 1; step >>= 1) {
+#pragma unroll
+                for (int i = 0; i < kPerLane; ++i) {
+                    const int probe = kk[i] + step;
+                    if (probe <= N && (int)sR[probe - 1] <= Lv[i]) kk[i] = probe;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i) {
+                float2 gh = head;
+                if (kk[i] > 0) gh = kStage ? sGH[kk[i] - 1] : GH[kk[i] - 1];
+                const float Lf = (float)Lv[i];
+                const float tri = Lf * (Lf - 1.0f) * 0.5f;
+                tile[(lane + kWave * i) * (kMemoP + 1) + pi] = fmaf(Lf, gh.y, gh.x) + tri * (gam * (float)(N - kk[i] + 1));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kPerLane; ++i) tile[(lane + kWave * i) * (kMemoP + 1) + pi] = __builtin_inff();
+        }
+        __syncthreads();
+        const int col = tid % kMemoP;
+#pragma unroll
+        for (int it = 0; it < kMemoU * kMemoP / kMemoBlock; ++it) {
+            const int ul = tid / kMemoP + (kMemoBlock / kMemoP) * it;
+            const int u = u0 + ul;
+            if (u < U) a.memo[(size_t)u * a.m_pad + p0 + col] = tile[ul * (kMemoP + 1) + col];
+        }
+        __syncthreads();
     }
 }
 
@@ -653,14 +663,16 @@ bool set_lds(K kernel, size_t bytes)
 
 }  // namespace
 
-int memo_lds_stride(const gr_fleet* f) { return (f->tstride + 1) & ~1; }
+bool memo_staged(const gr_fleet* f) { return f->cap <= 512; }
 
-size_t memo_lds_bytes(const gr_fleet* f) { return (size_t)kMemoP * memo_lds_stride(f) * 2; }
+size_t memo_lds_bytes(const gr_fleet* f)
+{
+    return sizeof(float) * kMemoTile + (size_t)kMemoP * f->cap * (memo_staged(f) ? 10 : 2);
+}
 
 size_t score_lds_bytes(const gr_fleet* f)
 {
-    const size_t group = (size_t)f->bins * 4;
-    const size_t memo = memo_lds_bytes(f) + sizeof(float) * kMemoU * (kMemoP + 1);
+    const size_t group = (size_t)f->bins * 4, memo = memo_lds_bytes(f);
     return group > memo ? group : memo;
 }
 
@@ -669,7 +681,8 @@ int score_prepare(gr_fleet* f)
     const size_t hist = (size_t)((f->bins + 1) / 2) * 4, scat = (size_t)f->bins * 4;
     const bool ok = set_lds(k_hist<false>, hist) && set_lds(k_hist<true>, hist) &&
                     set_lds(k_scatter<false>, scat) && set_lds(k_scatter<true>, scat) &&
-                    set_lds(k_scan, scat) && set_lds(k_memo, memo_lds_bytes(f));
+                    set_lds(k_scan, scat) && set_lds(k_memo<false>, memo_lds_bytes(f)) &&
+                    set_lds(k_memo<true>, memo_lds_bytes(f));
     return ok ? GR_OK : GR_ERR_HIP;
 }
 
@@ -704,13 +717,18 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     const int64_t max_rows = n < bins ? n : bins;
     {
         MemoArgs m{};
-        m.totals = f->totals; m.row_len = f->row_len; m.order = f->order; m.hN = f->hN; m.hQ = f->hQ;
+        m.totals = f->totals; m.row_len = f->row_len; m.order = f->order; m.hN = f->hN;
         m.cls = f->cls; m.inst_class = f->inst_class;
-        m.tabR = f->tabR; m.tabG = f->tabG; m.tabS = f->tabS; m.memo = f->memo;
-        m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.tstride = f->tstride; m.lds_stride = memo_lds_stride(f);
+        m.tabR = f->tabR; m.tabGH = f->tabGH; m.headGH = f->headGH; m.memo = f->memo;
+        m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.cap = f->cap;
+        // every workgroup walks all lengths; with few instances the lengths are dealt out to several
+        const int gx = f->m_pad / kMemoP;
+        const int64_t chunks = (max_rows + kMemoU - 1) / kMemoU;
+        int gy = gx >= 256 ? 1 : 256 / gx;
+        if (gy > chunks) gy = (int)chunks;
         ProfScope ps(f, kMemoRoute + off, s);
-        hipLaunchKernelGGL(k_memo, dim3(f->m_pad / kMemoP, (unsigned)((max_rows + kMemoU - 1) / kMemoU)),
-                           dim3(kMemoBlock), memo_lds_bytes(f), s, m);
+        if (memo_staged(f)) hipLaunchKernelGGL(k_memo<true>, dim3(gx, gy), dim3(kMemoBlock), memo_lds_bytes(f), s, m);
+        else hipLaunchKernelGGL(k_memo<false>, dim3(gx, gy), dim3(kMemoBlock), memo_lds_bytes(f), s, m);
     }
     {
         TileArgs t{};

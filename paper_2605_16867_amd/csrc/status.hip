@@ -1,27 +1,21 @@
-// Status build (step 1 of the path): per instance, an LDS radix sort of the
-// remaining lengths, three integer prefix sums over the sorted order, and from
-// them the finish time of every held request (Sec. 3.4's "expected finish
-// time"), q_g and d_g of Eq. 2, and the instance table used for scoring; then
-// the capability order of Alg. 1's argmax d_g.
+// Status build (step 1 of the path): per instance, a sort of the remaining
+// lengths, three integer prefix sums over the sorted order, and from them the
+// finish time of every held request (Sec. 3.4's "expected finish time"), q_g
+// and d_g of Eq. 2, and the instance table used for scoring; then the
+// capability order of Alg. 1's argmax d_g.
+//
+// One wave per instance, everything in registers: the wave holds 64 * kEPL sort
+// words (remaining length in the high bits, entry index in the low bits, so
+// all words differ and the order is stable), kEPL consecutive positions of the
+// sorted order per lane.  A bitonic network sorts them: exchanges inside a lane
+// are a min/max pair, exchanges between lanes fetch the partner's word through
+// the LDS crossbar (ds_bpermute) and keep the smaller or the larger of the two
+// with one median-of-three against 0 or 0xFFFFFFFF.  No barriers, no atomics.
 #include "common.h"
 
 namespace gr {
 namespace {
 
-// Lanes of the wave whose 8-bit digit equals this lane's, among `valid` lanes.
-__device__ inline unsigned long long match_digit(unsigned digit, bool valid)
-{
-    unsigned long long m = __ballot(valid);
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {
-        const bool bit = (digit >> b) & 1u;
-        const unsigned long long bb = __ballot(bit);
-        m &= bit ? bb : ~bb;
-    }
-    return m;
-}
-
-// ------------------------------------------------------------------ status build
 struct BuildArgs {
     const int *act_off, *act_prompt, *act_gen, *act_rem;
     const int *q_off, *q_prompt, *q_len;
@@ -31,73 +25,104 @@ struct BuildArgs {
     uint8_t* out_flag;
     const ClassCoef* cls;
     const int* inst_class;
-    int* tabR;
-    float *tabG, *tabS;
+    uint16_t* tabR;
+    float2* tabGH;
+    float2* headGH;
     int* hN;
-    double* hQ;
     double* hD;
     int* act_inst;
     int* rank_acc;
     int* counters;
     int64_t n_active, n_queued;
-    int max_entries, ncap, tstride, idx_bits, key_bits, max_len;
+    int n_inst, max_entries, max_len;
 };
 
-// One stable counting pass of the LSD radix sort over an 8-bit digit.  Each
-// wave owns a contiguous run of 64-entry chunks, so "wave, then chunk, then
-// lane" is the entry order and per-wave digit counters keep the pass stable.
-__device__ inline void radix_pass(const uint32_t* src, uint32_t* dst, uint32_t* cnt,
-                                  uint32_t* wsum, int n, int shift, int c_begin, int c_end)
+// (No DPP instruction may read a register this writes within two instructions;
+// this file uses none.)
+__device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t b, uint32_t c)
 {
-    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) cnt[w * 256 + tid] = 0;
-    __syncthreads();
-    for (int c = c_begin; c < c_end; ++c) {
-        const int i = c * kWave + lane;
-        if (i < n) atomicAdd(&cnt[wave * 256 + ((src[i] >> shift) & 0xFFu)], 1u);
-    }
-    __syncthreads();
-    {   // thread t owns digit t: exclusive scan over (digit, wave)
-        uint32_t c[kWaves], tot = 0;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) { c[w] = cnt[w * 256 + tid]; tot += c[w]; }
-        const uint32_t incl = wave_incl_scan(tot);
-        if (lane == kWave - 1) wsum[wave] = incl;
-        __syncthreads();
-        uint32_t base = incl - tot;
-        for (int w = 0; w < wave; ++w) base += wsum[w];
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) { cnt[w * 256 + tid] = base; base += c[w]; }
-    }
-    __syncthreads();
-    for (int c = c_begin; c < c_end; ++c) {
-        const int i = c * kWave + lane;
-        const bool valid = i < n;
-        const uint32_t word = valid ? src[i] : 0u;
-        const unsigned digit = (word >> shift) & 0xFFu;
-        const unsigned long long m = match_digit(digit, valid);
-        const unsigned long long below = m & ((1ull << lane) - 1ull);
-        uint32_t old = 0;
-        if (valid && below == 0ull) old = atomicAdd(&cnt[wave * 256 + digit], (uint32_t)__popcll(m));
-        const int leader = valid ? __ffsll((long long)m) - 1 : lane;
-        old = __shfl(old, leader, kWave);
-        if (valid) dst[old + __popcll(below)] = word;
-    }
-    __syncthreads();
+    uint32_t o;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(o) : "v"(a), "v"(b), "v"(c));
+    return o;
 }
 
+// The partner lane's copy of x; lane4 = 4 * lane, mask = lane XOR distance.
+__device__ __forceinline__ uint32_t fetch_xor(uint32_t x, int mask, int lane4)
+{
+    return (uint32_t)__builtin_amdgcn_ds_bpermute(lane4 ^ (mask << 2), (int)x);
+}
+
+__device__ __forceinline__ void order2(uint32_t& lo, uint32_t& hi)
+{
+    const uint32_t a = lo, b = hi;
+    lo = a < b ? a : b;
+    hi = a < b ? b : a;
+}
+
+// Ascending bitonic sort of 64 * kEPL words, word v = lane * kEPL + r in key[r].
+// Stage k merges sorted runs of k/2 into runs of k: first v against its mirror
+// image v ^ (k-1) in the run, then distances k/4, k/8, .. 1; the lower position
+// always keeps the smaller word.
+template <int kEPL>
+__device__ __forceinline__ void bitonic_sort(uint32_t (&key)[kEPL], int lane)
+{
+    const int lane4 = lane << 2;
+    constexpr int kCap = kWave * kEPL;
+#pragma unroll
+    for (int k = 2; k <= kCap; k <<= 1) {
+        if (k <= kEPL) {
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r)
+                if (r < (r ^ (k - 1))) order2(key[r], key[r ^ (k - 1)]);
+        } else {
+            const int lm = k / kEPL - 1;
+            const uint32_t bound = (lane & (k / kEPL / 2)) ? 0xFFFFFFFFu : 0u;   // upper partner keeps the larger
+            uint32_t p[kEPL];
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r) p[r] = fetch_xor(key[kEPL - 1 - r], lm, lane4);
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r) key[r] = med3_u32(key[r], p[r], bound);
+        }
+#pragma unroll
+        for (int j = k / 4; j >= 1; j >>= 1) {
+            if (j < kEPL) {
+#pragma unroll
+                for (int r = 0; r < kEPL; ++r)
+                    if ((r & j) == 0) order2(key[r], key[r | j]);
+            } else {
+                const int lm = j / kEPL;
+                const uint32_t bound = (lane & lm) ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+                for (int r = 0; r < kEPL; ++r) key[r] = med3_u32(key[r], fetch_xor(key[r], lm, lane4), bound);
+            }
+        }
+    }
+}
+
+// Exclusive prefix over the lanes of a wave, and the total.
+__device__ __forceinline__ long long wave_excl_scan(long long v, long long& total)
+{
+    const long long incl = wave_incl_scan(v);
+    total = __shfl(incl, kWave - 1, kWave);
+    return incl - v;
+}
+
+constexpr int kBuildWaves = kBlock / kWave;
+
+constexpr int log2_of(int v) { return v <= 1 ? 0 : 1 + log2_of(v / 2); }
+
+template <int kEPL>
 __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
 {
     extern __shared__ uint32_t smem[];
-    uint32_t* keyA = smem;
-    uint32_t* keyB = keyA + a.ncap;
-    int* ctx = reinterpret_cast<int*>(keyB + a.ncap);
-    uint32_t* cnt = reinterpret_cast<uint32_t*>(ctx + a.ncap);  // [kWaves][256]
-    __shared__ long long red[kWaves][3];
-    __shared__ uint32_t wsum[kWaves];
+    constexpr int kCap = kWave * kEPL;
+    constexpr int kIdxBits = log2_of(kCap);
+    constexpr uint32_t kIdxMask = (1u << kIdxBits) - 1u;
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int g = blockIdx.x * kBuildWaves + wave;
+    if (g >= a.n_inst) return;
+    int* ctx = reinterpret_cast<int*>(smem) + wave * kCap;     // this wave's contexts, by entry index
 
-    const int g = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / kWave;
     const ClassCoef cc = a.cls[a.inst_class[g]];
     // offsets are clamped into the arrays, so broken CSR data cannot index outside them
     const int a0 = (int)min((int64_t)max(a.act_off[g], 0), a.n_active);
@@ -109,100 +134,117 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     if (Q > a.max_entries - A) { Q = a.max_entries - A; status |= GR_DEV_ENTRIES_DROPPED; }
     const int N = A + Q;
 
-    // load: one sort word per entry = (remaining length << idx_bits) | entry index
-    long long csum = 0, qsum = 0;
-    for (int i = tid; i < N; i += kBlock) {
-        int rem, c;
-        if (i < A) {
-            rem = a.act_rem[a0 + i];
-            c = a.act_prompt[a0 + i] + a.act_gen[a0 + i];
-            a.act_inst[a0 + i] = g;
-        } else {
-            rem = a.q_len[q0 + i - A];
-            c = a.q_prompt[q0 + i - A];
-            qsum += c;
+    // load, entry i = 64 r + lane: one sort word per entry = (remaining length << kIdxBits) | i
+    uint32_t key[kEPL];
+    long long qsum = 0;
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) {
+        const int i = r * kWave + lane;
+        uint32_t word = 0xFFFFFFFFu;        // past the last entry: sorts to the end
+        if (i < N) {
+            int rem, c;
+            if (i < A) {
+                rem = a.act_rem[a0 + i];
+                c = a.act_prompt[a0 + i] + a.act_gen[a0 + i];
+                a.act_inst[a0 + i] = g;
+            } else {
+                rem = a.q_len[q0 + i - A];
+                c = a.q_prompt[q0 + i - A];
+                qsum += c;
+            }
+            if (rem < 0 || rem > a.max_len) { rem = min(max(rem, 0), a.max_len); status |= GR_DEV_LEN_CLAMPED; }
+            word = ((uint32_t)rem << kIdxBits) | (uint32_t)i;
+            ctx[i] = c;
         }
-        if (rem < 0 || rem > a.max_len) { rem = min(max(rem, 0), a.max_len); status |= GR_DEV_LEN_CLAMPED; }
-        keyA[i] = ((uint32_t)rem << a.idx_bits) | (uint32_t)i;
-        ctx[i] = c;
-        csum += c;
+        key[r] = word;
     }
     if (status) atomicOr(&a.counters[0], status);
-    csum = wave_sum(csum);
-    qsum = wave_sum(qsum);
-    if (lane == 0) { red[wave][0] = csum; red[wave][1] = qsum; }
-    __syncthreads();
-    long long Ctot = 0, Qtot = 0;
+    if (Q > 0) qsum = wave_sum(qsum);       // Q is the same in every lane
+    const double q = cc.delta * (double)qsum;
+
+    bitonic_sort<kEPL>(key, lane);
+
+    // the wave's own LDS writes above must be visible to its reads below
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // sorted position v = lane * kEPL + r; entries first, in order of remaining length
+    int R[kEPL], cx[kEPL], idx[kEPL];
+    long long yl = 0, xl = 0, cl = 0;       // this lane's sums of R, c*R + tri(R), c
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) { Ctot += red[w][0]; Qtot += red[w][1]; }
-    __syncthreads();
-
-    const int nchunks = (N + kWave - 1) / kWave;
-    const int cpw = (nchunks + kWaves - 1) / kWaves;
-    const int c_begin = min(wave * cpw, nchunks), c_end = min(c_begin + cpw, nchunks);
-
-    uint32_t *src = keyA, *dst = keyB;
-    for (int shift = a.idx_bits; shift < a.idx_bits + a.key_bits; shift += 8) {
-        radix_pass(src, dst, cnt, wsum, N, shift, c_begin, c_end);
-        uint32_t* t = src; src = dst; dst = t;
+    for (int r = 0; r < kEPL; ++r) {
+        const bool valid = lane * kEPL + r < N;
+        idx[r] = (int)(key[r] & kIdxMask);
+        R[r] = valid ? (int)(key[r] >> kIdxBits) : 0;
+        cx[r] = valid ? ctx[idx[r]] : 0;
+        yl += R[r];
+        xl += (long long)cx[r] * R[r] + (long long)(R[r] * (R[r] - 1) / 2);
+        cl += cx[r];
     }
+    long long Ytot, Xtot, Ctot;
+    long long Y = wave_excl_scan(yl, Ytot), X = wave_excl_scan(xl, Xtot), Pc = wave_excl_scan(cl, Ctot);
 
-    // integer prefix sums over the sorted order: a reduction per wave, then a scan
-    const uint32_t idx_mask = (1u << a.idx_bits) - 1u;
-    long long sY = 0, sX = 0, sC = 0;
-    for (int c = c_begin; c < c_end; ++c) {
-        const int pos = c * kWave + lane;
-        if (pos < N) {
-            const uint32_t word = src[pos];
-            const long long R = word >> a.idx_bits, cx = ctx[word & idx_mask];
-            sY += R; sX += cx * R + R * (R - 1) / 2; sC += cx;
-        }
-    }
-    sY = wave_sum(sY); sX = wave_sum(sX); sC = wave_sum(sC);
-    if (lane == 0) { red[wave][0] = sY; red[wave][1] = sX; red[wave][2] = sC; }
-    __syncthreads();
-    long long cY = 0, cX = 0, cC = 0;   // carries: totals of the waves before this one
-    for (int w = 0; w < wave; ++w) { cY += red[w][0]; cX += red[w][1]; cC += red[w][2]; }
-
-    const double q = cc.delta * (double)Qtot;
-    const size_t tb = (size_t)g * a.tstride;
-    for (int c = c_begin; c < c_end; ++c) {
-        const int pos = c * kWave + lane;
-        const bool valid = pos < N;
-        long long R = 0, cx = 0;
-        uint32_t idx = 0;
+    // table entry v describes the segment after the v+1 shortest requests, n of them still running:
+    //   E_g(L) = Gq + L * H + tri(L) * gamma * (n + 1)
+    //   Gq = q + beta * Y + gamma * X,   H = alpha + beta * (n + 1) + gamma * S
+    uint16_t tR[kEPL];
+    float2 tGH[kEPL];
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) {
+        const int v = lane * kEPL + r;
+        const bool valid = v < N;
+        const long long Rr = R[r], triR = (long long)(R[r] * (R[r] - 1) / 2);
+        Y += Rr;
+        X += (long long)cx[r] * Rr + triR;
+        Pc += cx[r];
+        const double n_after = (double)(N - v - 1), S_next = (double)(Ctot - Pc);
+        const double Yd = (double)Y, Xd = (double)X, Rd = (double)Rr;
+        tR[r] = valid ? (uint16_t)R[r] : (uint16_t)0xFFFFu;
+        tGH[r] = make_float2((float)(q + (cc.beta * Yd + cc.gamma * Xd)),
+                             (float)(cc.alpha + (cc.beta * (n_after + 1.0) + cc.gamma * S_next)));
         if (valid) {
-            const uint32_t word = src[pos];
-            R = word >> a.idx_bits; idx = word & idx_mask; cx = ctx[idx];
-        }
-        const long long triR = R * (R - 1) / 2;
-        const long long Y = wave_incl_scan(R) + cY;
-        const long long X = wave_incl_scan(cx * R + triR) + cX;
-        const long long Pc = wave_incl_scan(cx) + cC;
-        cY = __shfl(Y, kWave - 1, kWave); cX = __shfl(X, kWave - 1, kWave); cC = __shfl(Pc, kWave - 1, kWave);
-        if (valid) {
-            const int k = pos + 1;
-            const long long S_next = Ctot - Pc, n_after = N - k;
-            a.tabR[tb + k] = (int)R;
-            a.tabG[tb + k] = (float)(cc.beta * (double)Y + cc.gamma * (double)X);
-            a.tabS[tb + k] = (float)S_next;
-            const long long I1 = Y + n_after * R;
-            const long long I2 = X + R * S_next + n_after * triR;
-            const double fin = q + fma(cc.gamma, (double)I2, fma(cc.beta, (double)I1, cc.alpha * (double)R));
-            if (idx < (uint32_t)A) {
-                a.out_act_finish[a0 + idx] = (float)fin;
-                if (a.act_budget) a.out_flag[a0 + idx] = fin > (double)a.act_budget[a0 + idx];
+            // every product below is an integer below 2^53: exact
+            const double I1 = Yd + n_after * Rd;
+            const double I2 = Xd + Rd * S_next + n_after * (double)triR;
+            const double fin = q + fma(cc.gamma, I2, fma(cc.beta, I1, cc.alpha * Rd));
+            if (idx[r] < A) {
+                a.out_act_finish[a0 + idx[r]] = (float)fin;
+                if (a.act_budget) a.out_flag[a0 + idx[r]] = fin > (double)a.act_budget[a0 + idx[r]];
             } else if (a.out_q_finish) {
-                a.out_q_finish[q0 + idx - A] = (float)fin;
+                a.out_q_finish[q0 + idx[r] - A] = (float)fin;
             }
         }
     }
-    if (tid == 0) {
-        a.tabR[tb] = 0; a.tabG[tb] = 0.f; a.tabS[tb] = (float)Ctot;
+    {
+        uint16_t* dstR = a.tabR + (size_t)g * kCap + lane * kEPL;
+        float2* dstGH = a.tabGH + (size_t)g * kCap + lane * kEPL;
+        if constexpr (kEPL >= 8) {
+#pragma unroll
+            for (int r = 0; r < kEPL; r += 8) {
+                uint4 w;
+                w.x = tR[r] | ((uint32_t)tR[r + 1] << 16); w.y = tR[r + 2] | ((uint32_t)tR[r + 3] << 16);
+                w.z = tR[r + 4] | ((uint32_t)tR[r + 5] << 16); w.w = tR[r + 6] | ((uint32_t)tR[r + 7] << 16);
+                *reinterpret_cast<uint4*>(dstR + r) = w;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r) dstR[r] = tR[r];
+        }
+        if constexpr (kEPL >= 2) {
+#pragma unroll
+            for (int r = 0; r < kEPL; r += 2)
+                *reinterpret_cast<float4*>(dstGH + r) = make_float4(tGH[r].x, tGH[r].y, tGH[r + 1].x, tGH[r + 1].y);
+        } else {
+            dstGH[0] = tGH[0];
+        }
+    }
+    if (lane == 0) {
+        const double Cd = (double)Ctot;
+        a.headGH[g] = make_float2((float)q, (float)(cc.alpha + (cc.beta * (double)(N + 1) + cc.gamma * Cd)));
         a.hN[g] = N;
-        a.hQ[g] = q;
         a.rank_acc[g] = 0;
-        const double d = fma(cc.gamma, (double)Ctot, fma(cc.beta, (double)N, cc.alpha));
+        const double d = fma(cc.gamma, Cd, fma(cc.beta, (double)N, cc.alpha));
         a.hD[g] = d;
         if (a.out_d) a.out_d[g] = d;
     }
@@ -252,16 +294,14 @@ __global__ __launch_bounds__(kBlock) void k_rank_final(const int* __restrict__ r
     }
 }
 
-}  // namespace
-
-size_t status_lds_bytes(const gr_fleet* f) { return (size_t)f->ncap * 12 + kWaves * 256 * 4; }
-
-int status_prepare(gr_fleet* f)
+template <int kEPL>
+void launch_build(const BuildArgs& b, int M, hipStream_t s)
 {
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(k_build),
-                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)status_lds_bytes(f)) == hipSuccess ? GR_OK : GR_ERR_HIP;
+    hipLaunchKernelGGL(k_build<kEPL>, dim3((M + kBuildWaves - 1) / kBuildWaves), dim3(kBlock),
+                       (size_t)kBuildWaves * kWave * kEPL * sizeof(int), s, b);
 }
+
+}  // namespace
 
 int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
 {
@@ -272,16 +312,22 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
     b.out_act_finish = in.out_act_finish; b.out_q_finish = in.out_q_finish;
     b.out_d = in.out_d; b.out_flag = in.out_flag;
     b.cls = f->cls; b.inst_class = f->inst_class;
-    b.tabR = f->tabR; b.tabG = f->tabG; b.tabS = f->tabS;
-    b.hN = f->hN; b.hQ = f->hQ; b.hD = f->hD; b.act_inst = f->act_inst;
+    b.tabR = f->tabR; b.tabGH = f->tabGH; b.headGH = f->headGH;
+    b.hN = f->hN; b.hD = f->hD; b.act_inst = f->act_inst;
     b.rank_acc = f->rank_acc; b.counters = f->counters;
     b.n_active = in.n_active; b.n_queued = in.n_queued;
-    b.max_entries = f->max_entries; b.ncap = f->ncap; b.tstride = f->tstride;
-    b.idx_bits = f->idx_bits; b.key_bits = f->key_bits; b.max_len = f->max_len;
+    b.n_inst = f->n_inst; b.max_entries = f->max_entries; b.max_len = f->max_len;
     const int M = f->n_inst;
     {
         ProfScope ps(f, kBuild, s);
-        hipLaunchKernelGGL(k_build, dim3(M), dim3(kBlock), status_lds_bytes(f), s, b);
+        switch (f->epl) {
+            case 1: launch_build<1>(b, M, s); break;
+            case 2: launch_build<2>(b, M, s); break;
+            case 4: launch_build<4>(b, M, s); break;
+            case 8: launch_build<8>(b, M, s); break;
+            case 16: launch_build<16>(b, M, s); break;
+            default: launch_build<32>(b, M, s); break;
+        }
     }
     {
         ProfScope ps(f, kRankCount, s);
