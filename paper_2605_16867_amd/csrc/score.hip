@@ -202,25 +202,23 @@ struct MemoArgs {
 
 // E of every (distinct length, instance).  A workgroup of kMemoP waves takes
 // kMemoP consecutive positions of the capability order, one instance per wave:
-// the wave copies the instance's sorted lengths (and, with kStage, its segment
-// coefficients) to LDS once, then walks the distinct lengths kMemoU at a time;
-// a lane takes a length, finds its segment k = #{R_i <= L} by binary search in
-// LDS and evaluates the segment's quadratic.  Each pass is turned in LDS so
-// that the table is written in runs of kMemoP positions per length.
+// the wave copies the instance's sorted lengths to LDS once, then walks the
+// distinct lengths kMemoU at a time; a lane takes a length, finds its segment
+// k = #{R_i <= L} by binary search in LDS and evaluates the segment's quadratic
+// (the coefficients of neighbouring lengths share cache lines).  Each pass is
+// turned in LDS, in one of two buffers so that one barrier per pass is enough,
+// and written in runs of kMemoP positions per length.
 constexpr int kMemoBlock = kMemoP * kWave;
 constexpr int kMemoTile = kMemoU * (kMemoP + 1);       // floats
 
-template <bool kStage>
 __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
 {
     extern __shared__ uint32_t lds[];
-    float* tile = reinterpret_cast<float*>(lds);
+    float* tiles = reinterpret_cast<float*>(lds);
     const int U = a.totals[1];
     const int p0 = blockIdx.x * kMemoP;
     const int tid = threadIdx.x, lane = lane_id(), pi = tid / kWave;
-    uint16_t* sR = reinterpret_cast<uint16_t*>(tile + kMemoTile) + (size_t)pi * a.cap;
-    float2* sGH = reinterpret_cast<float2*>(reinterpret_cast<uint16_t*>(tile + kMemoTile) + (size_t)kMemoP * a.cap)
-                  + (size_t)pi * a.cap;
+    uint16_t* sR = reinterpret_cast<uint16_t*>(tiles + 2 * kMemoTile) + (size_t)pi * a.cap;
     constexpr int kPerLane = kMemoU / kWave;
     const int p = p0 + pi;
     const int g = p < a.n_inst ? a.order[p] : -1;
@@ -235,16 +233,14 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
         GH = a.tabGH + (size_t)g * a.cap;
         const uint4* srcR = reinterpret_cast<const uint4*>(a.tabR + (size_t)g * a.cap);
         for (int c = lane; c * 8 < N; c += kWave) reinterpret_cast<uint4*>(sR)[c] = srcR[c];
-        if (kStage) {
-            const float4* srcG = reinterpret_cast<const float4*>(GH);
-            for (int c = lane; c * 2 < N; c += kWave) reinterpret_cast<float4*>(sGH)[c] = srcG[c];
-        }
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    for (int u0 = blockIdx.y * kMemoU; u0 < U; u0 += gridDim.y * kMemoU) {
+    int buf = 0;
+    for (int u0 = blockIdx.y * kMemoU; u0 < U; u0 += gridDim.y * kMemoU, buf ^= 1) {
+        float* tile = tiles + buf * kMemoTile;
         if (g >= 0) {
             int Lv[kPerLane], kk[kPerLane];
 #pragma unroll
@@ -264,7 +260,7 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
 #pragma unroll
             for (int i = 0; i < kPerLane; ++i) {
                 float2 gh = head;
-                if (kk[i] > 0) gh = kStage ? sGH[kk[i] - 1] : GH[kk[i] - 1];
+                if (kk[i] > 0) gh = GH[kk[i] - 1];
                 const float Lf = (float)Lv[i];
                 const float tri = Lf * (Lf - 1.0f) * 0.5f;
                 tile[(lane + kWave * i) * (kMemoP + 1) + pi] = fmaf(Lf, gh.y, gh.x) + tri * (gam * (float)(N - kk[i] + 1));
@@ -273,7 +269,7 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
 #pragma unroll
             for (int i = 0; i < kPerLane; ++i) tile[(lane + kWave * i) * (kMemoP + 1) + pi] = __builtin_inff();
         }
-        __syncthreads();
+        __syncthreads();     // the other buffer was last read before the previous pass's barrier
         const int col = tid % kMemoP;
 #pragma unroll
         for (int it = 0; it < kMemoU * kMemoP / kMemoBlock; ++it) {
@@ -281,7 +277,6 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
             const int u = u0 + ul;
             if (u < U) a.memo[(size_t)u * a.m_pad + p0 + col] = tile[ul * (kMemoP + 1) + col];
         }
-        __syncthreads();
     }
 }
 
@@ -384,30 +379,60 @@ struct RowView {
     int nblk;                          // blocks of 64 positions (even)
 };
 
+// The walks below visit the blocks of a row in order; each depends on what the
+// previous block showed, so their loads are taken a few blocks at a time, the
+// next chunk in flight while the current one is looked at.
+template <int kN, bool kWithOrder>
+struct Chunk {
+    float e[kN];
+    float2 k[kN];
+    int g[kWithOrder ? kN : 1];
+};
+
+template <int kN, bool kWithOrder>
+__device__ __forceinline__ void load_chunk(const RowView& rv, int b0, int lane, Chunk<kN, kWithOrder>& c)
+{
+#pragma unroll
+    for (int i = 0; i < kN; ++i) {
+        const int p = min(b0 + i, rv.nblk - 1) * kWave + lane;    // past the end: the last block again
+        c.e[i] = rv.E[p];
+        c.k[i] = rv.posK[p];
+        if (kWithOrder) c.g[i] = rv.order[p];
+    }
+}
+
 // First feasible position in capability order for the few requests of a tile
 // that have one (bit j of `fm`): blocks in order, the requests still open one
 // after the other.  Exclusions are not applied here.
 __device__ inline void first_feasible_sparse(const RowView& rv, float rec_c0, float Dc, unsigned long long fm,
                                              int lane, int& foundP, float& foundT)
 {
-    float En = rv.E[lane];
-    float2 Kn = rv.posK[lane];
-    for (int b = 0; b < rv.nblk && fm; ++b) {
-        const float e = En, k = kappa_of(Kn, rv.Lf);
-        if (b + 1 < rv.nblk) { En = rv.E[(b + 1) * kWave + lane]; Kn = rv.posK[(b + 1) * kWave + lane]; }
-        unsigned long long m = fm;
-        while (m) {
-            const int j = __ffsll((long long)m) - 1;
-            m &= m - 1;
-            const float T = fmaf(readlane_f(rec_c0, j), k, e);
-            const unsigned long long feas = __ballot(T <= readlane_f(Dc, j));
-            if (feas) {
-                const int fl = __ffsll((long long)feas) - 1;
-                const float Tf = readlane_f(T, fl);
-                if (lane == j) { foundP = b * kWave + fl; foundT = Tf; }
-                fm &= ~(1ull << j);
+    constexpr int kChunk = 8;
+    Chunk<kChunk, false> cur;
+    load_chunk(rv, 0, lane, cur);
+    for (int b0 = 0; b0 < rv.nblk && fm; b0 += kChunk) {
+        Chunk<kChunk, false> nxt;
+        load_chunk(rv, b0 + kChunk, lane, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            if (b0 + i >= rv.nblk) break;
+            const float e = cur.e[i], k = kappa_of(cur.k[i], rv.Lf);
+            unsigned long long m = fm;
+            while (m) {
+                const int j = __ffsll((long long)m) - 1;
+                m &= m - 1;
+                const float T = fmaf(readlane_f(rec_c0, j), k, e);
+                const unsigned long long feas = __ballot(T <= readlane_f(Dc, j));
+                if (feas) {
+                    const int fl = __ffsll((long long)feas) - 1;
+                    const float Tf = readlane_f(T, fl);
+                    if (lane == j) { foundP = (b0 + i) * kWave + fl; foundT = Tf; }
+                    fm &= ~(1ull << j);
+                }
             }
         }
+        cur = nxt;
     }
 }
 
@@ -424,29 +449,40 @@ __device__ inline void first_feasible_dense(const RowView& rv, const float (&c0)
         asm volatile("" : "+v"(D[j]));     // 32 more scalars would not fit the scalar file
     }
     unsigned left = (unsigned)fm;
-    float En = rv.E[lane];
-    float2 Kn = rv.posK[lane];
-    for (int b = 0; b < rv.nblk && left; ++b) {
-        float e = En, k = kappa_of(Kn, rv.Lf);
-        if (b + 1 < rv.nblk) { En = rv.E[(b + 1) * kWave + lane]; Kn = rv.posK[(b + 1) * kWave + lane]; }
-        unsigned long long any = 0;
+    constexpr int kChunk = 2;
+    Chunk<kChunk, false> cur;
+    load_chunk(rv, 0, lane, cur);
+    for (int b0 = 0; b0 < rv.nblk && left; b0 += kChunk) {
+        Chunk<kChunk, false> nxt;
+        load_chunk(rv, b0 + kChunk, lane, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < kChunk && b0 + i < rv.nblk && left; ++i) {
+            float e = 0.f;
+            float2 kk = make_float2(0.f, 0.f);
 #pragma unroll
-        for (int j = 0; j < kTileReq; ++j) any |= __ballot(fmaf(c0[j], k, e) <= D[j]);
-        if (any) {
-            asm volatile("" : "+v"(e), "+v"(k));   // recomputed: nothing of this branch stays live above
+            for (int c = 0; c < kChunk; ++c)
+                if (c == i) { e = cur.e[c]; kk = cur.k[c]; }
+            float k = kappa_of(kk, rv.Lf);
+            unsigned long long any = 0;
 #pragma unroll
-            for (int j = 0; j < kTileReq; ++j) {
-                const float T = fmaf(c0[j], k, e);
-                const unsigned long long feas = __ballot(T <= D[j]);
-                if (feas) {
-                    const int fl = __ffsll((long long)feas) - 1;
-                    const float Tf = readlane_f(T, fl);
-                    if (lane == j) { foundP = b * kWave + fl; foundT = Tf; }
-                    left &= ~(1u << j);
-                    D[j] = -__builtin_inff();
+            for (int j = 0; j < kTileReq; ++j) any |= __ballot(fmaf(c0[j], k, e) <= D[j]);
+            if (any) {
+                asm volatile("" : "+v"(e), "+v"(k));   // recomputed: nothing of this branch stays live above
+#pragma unroll
+                for (int j = 0; j < kTileReq; ++j) {
+                    const float T = fmaf(c0[j], k, e);
+                    const unsigned long long feas = __ballot(T <= D[j]);
+                    if (feas) {
+                        const int fl = __ffsll((long long)feas) - 1;
+                        const float Tf = readlane_f(T, fl);
+                        if (lane == j) { foundP = (b0 + i) * kWave + fl; foundT = Tf; }
+                        left &= ~(1u << j);
+                        D[j] = -__builtin_inff();
+                    }
                 }
             }
         }
+        cur = nxt;
     }
 }
 
@@ -460,20 +496,31 @@ __device__ inline void exact_choice(const RowView& rv, float c0, float D, int pe
     float minT = __builtin_inff();
     int minP = -1, minG = 0x7fffffff;
     found = false;
-    for (int b = 0; b < rv.nblk; ++b) {
-        const int p = b * kWave + lane;
-        const int g = rv.order[p];
-        float T = fmaf(c0, kappa_of(rv.posK[p], rv.Lf), rv.E[p]);
-        if (p == pex || g < 0) T = __builtin_inff();
-        const unsigned long long feas = __ballot(T <= D);
-        if (feas) {
-            const int fl = __ffsll((long long)feas) - 1;
-            pos = b * kWave + fl;
-            val = readlane_f(T, fl);
-            found = true;
-            return;
+    constexpr int kChunk = 4;
+    Chunk<kChunk, true> cur;
+    load_chunk(rv, 0, lane, cur);
+    for (int b0 = 0; b0 < rv.nblk; b0 += kChunk) {
+        Chunk<kChunk, true> nxt;
+        load_chunk(rv, b0 + kChunk, lane, nxt);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kChunk; ++i) {
+            if (b0 + i >= rv.nblk) break;
+            const int p = (b0 + i) * kWave + lane;
+            const int g = cur.g[i];
+            float T = fmaf(c0, kappa_of(cur.k[i], rv.Lf), cur.e[i]);
+            if (p == pex || g < 0) T = __builtin_inff();
+            const unsigned long long feas = __ballot(T <= D);
+            if (feas) {
+                const int fl = __ffsll((long long)feas) - 1;
+                pos = (b0 + i) * kWave + fl;
+                val = readlane_f(T, fl);
+                found = true;
+                return;
+            }
+            if (T < minT || (T == minT && g >= 0 && g < minG)) { minT = T; minP = p; minG = g; }
         }
-        if (T < minT || (T == minT && g >= 0 && g < minG)) { minT = T; minP = p; minG = g; }
+        cur = nxt;
     }
     const float Tm = wave_min(minT);
     unsigned long long cand = __ballot(minT == Tm && Tm < __builtin_inff());
@@ -553,22 +600,36 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
         minT[j] = __builtin_inff();
     }
 
-    // ---- main pass: two blocks of 64 positions per step
+    // ---- main pass: two blocks of 64 positions per step, operands of the next step in flight
+    // (two register sets taking turns, so that nothing is copied)
     {
-        float Ea = rv.E[lane], Eb = rv.E[kWave + lane];
-        float2 Ka = rv.posK[lane], Kb = rv.posK[kWave + lane];
-        for (int b = 0; b < rv.nblk; b += 2) {
-            const float ea = Ea, eb = Eb;
-            const float ka = kappa_of(Ka, rv.Lf), kb = kappa_of(Kb, rv.Lf);
-            if (b + 2 < rv.nblk) {
-                Ea = rv.E[(b + 2) * kWave + lane]; Eb = rv.E[(b + 3) * kWave + lane];
-                Ka = rv.posK[(b + 2) * kWave + lane]; Kb = rv.posK[(b + 3) * kWave + lane];
-            }
+        struct Step { float Ea, Eb; float2 Ka, Kb; };
+        auto fetch = [&](Step& st, int b) {
+            st.Ea = rv.E[b * kWave + lane]; st.Eb = rv.E[(b + 1) * kWave + lane];
+            st.Ka = rv.posK[b * kWave + lane]; st.Kb = rv.posK[(b + 1) * kWave + lane];
+        };
+        auto fold = [&](const Step& st) {
+            const float ka = kappa_of(st.Ka, rv.Lf), kb = kappa_of(st.Kb, rv.Lf);
 #pragma unroll
             for (int j = 0; j < kTileReq; ++j) {
-                const float Ta = fmaf(c0[j], ka, ea), Tb = fmaf(c0[j], kb, eb);
+                const float Ta = fmaf(c0[j], ka, st.Ea), Tb = fmaf(c0[j], kb, st.Eb);
                 minT[j] = fminf(fminf(minT[j], Ta), Tb);
             }
+        };
+        // the prefetch is unconditional (past the end it re-reads the last step), so that the
+        // compiler can count exactly how many loads may stay in flight at each use
+        Step s0, s1;
+        const int last = rv.nblk - 2;
+        fetch(s0, 0);
+        for (int b = 0; b < rv.nblk; b += 4) {
+            fetch(s1, min(b + 2, last));
+            __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the arithmetic
+            fold(s0);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(s0, min(b + 4, last));
+            __builtin_amdgcn_sched_barrier(0);
+            if (b + 2 < rv.nblk) fold(s1);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
@@ -601,13 +662,13 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     const int s_win = __shfl(win, src, kWave);
     int firstB = 0x7fffffff;
     if (__ballot(mine && foundP < 0)) {
-        const int lw = s_win & (kWave - 1);
-        const float* __restrict__ pe = rv.E + lw;
-        const float2* __restrict__ pk = rv.posK + lw;
-#pragma unroll 4
-        for (int b = lane >> 5; b < rv.nblk; b += 2) {
-            const float Tc = fmaf(s_c0, kappa_of(pk[b * kWave], rv.Lf), pe[b * kWave]);
-            if (Tc == s_Tm) firstB = min(firstB, b);
+        const int lw = s_win & (kWave - 1), half = lane >> 5;
+        const float* __restrict__ pe = rv.E + half * kWave + lw;
+        const float2* __restrict__ pk = rv.posK + half * kWave + lw;
+#pragma unroll 8
+        for (int i = 0; i < rv.nblk / 2; ++i) {       // block 2 i + half
+            const float Tc = fmaf(s_c0, kappa_of(pk[i * 2 * kWave], rv.Lf), pe[i * 2 * kWave]);
+            firstB = Tc == s_Tm ? min(firstB, 2 * i + half) : firstB;
         }
     }
     firstB = min(firstB, __shfl_xor(firstB, 32, kWave));
@@ -663,12 +724,7 @@ bool set_lds(K kernel, size_t bytes)
 
 }  // namespace
 
-bool memo_staged(const gr_fleet* f) { return f->cap <= 512; }
-
-size_t memo_lds_bytes(const gr_fleet* f)
-{
-    return sizeof(float) * kMemoTile + (size_t)kMemoP * f->cap * (memo_staged(f) ? 10 : 2);
-}
+size_t memo_lds_bytes(const gr_fleet* f) { return sizeof(float) * 2 * kMemoTile + (size_t)kMemoP * f->cap * 2; }
 
 size_t score_lds_bytes(const gr_fleet* f)
 {
@@ -681,8 +737,7 @@ int score_prepare(gr_fleet* f)
     const size_t hist = (size_t)((f->bins + 1) / 2) * 4, scat = (size_t)f->bins * 4;
     const bool ok = set_lds(k_hist<false>, hist) && set_lds(k_hist<true>, hist) &&
                     set_lds(k_scatter<false>, scat) && set_lds(k_scatter<true>, scat) &&
-                    set_lds(k_scan, scat) && set_lds(k_memo<false>, memo_lds_bytes(f)) &&
-                    set_lds(k_memo<true>, memo_lds_bytes(f));
+                    set_lds(k_scan, scat) && set_lds(k_memo, memo_lds_bytes(f));
     return ok ? GR_OK : GR_ERR_HIP;
 }
 
@@ -724,11 +779,10 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         // every workgroup walks all lengths; with few instances the lengths are dealt out to several
         const int gx = f->m_pad / kMemoP;
         const int64_t chunks = (max_rows + kMemoU - 1) / kMemoU;
-        int gy = gx >= 256 ? 1 : 256 / gx;
+        int gy = gx >= 512 ? 1 : 512 / gx;
         if (gy > chunks) gy = (int)chunks;
         ProfScope ps(f, kMemoRoute + off, s);
-        if (memo_staged(f)) hipLaunchKernelGGL(k_memo<true>, dim3(gx, gy), dim3(kMemoBlock), memo_lds_bytes(f), s, m);
-        else hipLaunchKernelGGL(k_memo<false>, dim3(gx, gy), dim3(kMemoBlock), memo_lds_bytes(f), s, m);
+        hipLaunchKernelGGL(k_memo, dim3(gx, gy), dim3(kMemoBlock), memo_lds_bytes(f), s, m);
     }
     {
         TileArgs t{};
