@@ -32,15 +32,20 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3  # 256 CU x 128 lanes x 2 flop x 2.4 GHz (packed
 
 # Algorithmic work per unit, independent of how the kernels are organised.
 # Scoring, per (request, instance) pair: Eq. 2 from per-(instance, length) terms
-# (one multiply-add = 2 flops), the feasibility compare of Alg. 1 (1), and the two
-# running selections, best capability among feasible and least latency (compare +
-# select each = 4): 7 operations, counted as flops.
-OPS_PER_PAIR = 7.0
+# (one multiply-add = 2 flops) and the pair's part in the selections of Alg. 1
+# (one comparison: the running least latency, which also decides feasibility
+# because the feasible set is non-empty exactly when the least latency meets the
+# deadline): 3 operations, counted as flops.
+OPS_PER_PAIR = 3.0
 # Status build, per held request: read prompt, generated, remaining (12 B), write
-# finish (4 B) and one table entry (12 B); the risk scan also reads the budget (4 B)
-# and writes the flag (1 B).
-BUILD_BYTES_PER_ENTRY = 28.0
+# finish (4 B) and one table entry (2 B sorted length + 8 B segment coefficients);
+# the risk scan also reads the budget (4 B) and writes the flag (1 B).
+BUILD_BYTES_PER_ENTRY = 26.0
 SCAN_EXTRA_BYTES_PER_ENTRY = 5.0
+# HBM bytes per launch of the dominant kernel (k_tile, migration launch of the "heavy" fleet) from
+# the rocprofv3 counter passes summarised under profiles/, scaled by the plain-copy calibration;
+# None whenever that kernel has changed since the counters were taken.
+TILE_MIGRATE_HEAVY_TRAFFIC_BYTES = None
 
 
 def parse():
@@ -114,8 +119,7 @@ def main():
               "(no collectives or sharding are part of this build)", file=sys.stderr)
         sys.exit(2)
     import torch
-    from paper_2605_16867_amd import workloads
-    from tests import parity
+    from paper_2605_16867_amd import binding, workloads
 
     fl = workloads.make_fleet(workloads.spec(a.config))
     M, R = fl.n_inst, len(fl.in_prompt)
@@ -123,8 +127,12 @@ def main():
     entries = na + nq
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    d = parity.upload(fl, dev)
-    h = parity.make_handle(fl)
+    d = {k: torch.from_numpy(np.ascontiguousarray(getattr(fl, k))).to(dev) for k in
+         ("act_off", "act_prompt", "act_gen", "act_rem", "act_rem_refreshed", "act_budget",
+          "q_off", "q_prompt", "q_len", "in_prompt", "in_len", "in_budget")}
+    h = binding.Fleet(fl.coef["delta"], fl.coef["alpha"], fl.coef["beta"], fl.coef["gamma"], fl.inst_class,
+                      max(int(max(np.diff(fl.act_off) + np.diff(fl.q_off))), 1), int(fl.spec.max_len),
+                      max(R, 1))
 
     fin = torch.empty(na, dtype=torch.float32, device=dev)
     inst = torch.empty(max(R, 1), dtype=torch.int32, device=dev)
@@ -191,8 +199,9 @@ def main():
     dominant = max((n for n in kernels if "bound" in kernels[n]),
                    key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
     dk = kernels[dominant]
+    traffic = TILE_MIGRATE_HEAVY_TRAFFIC_BYTES if (dominant == "k_tile<migrate>" and a.config == "heavy") else None
     roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
-                "unit": dk["unit"], "frac": dk["frac"], "traffic": None,
+                "unit": dk["unit"], "frac": dk["frac"], "traffic": traffic,
                 "avg_launch_ms": dk["avg_ms"]}
 
     out = {

@@ -75,8 +75,7 @@ enum {
  *   max_entries_per_inst      upper bound of active + queued requests on one instance
  *   max_len                   upper bound of any remaining / predicted decode length
  *   max_requests              upper bound of n_req of one gr_score_route call
- * Hard limits: bits(max_len) + bits(max_entries_per_inst) <= 32 (a length and
- * an entry index share one sort word); max_entries_per_inst <= 2048; max_len <= 32767.
+ * Hard limits: max_entries_per_inst <= 2048; max_len <= 32767.
  */
 int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
               const double* delta, const double* alpha, const double* beta, const double* gamma,

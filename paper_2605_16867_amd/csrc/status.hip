@@ -8,9 +8,10 @@
 // words (remaining length in the high bits, entry index in the low bits, so
 // all words differ and the order is stable), kEPL consecutive positions of the
 // sorted order per lane.  A bitonic network sorts them: exchanges inside a lane
-// are a min/max pair, exchanges between lanes fetch the partner's word through
-// the LDS crossbar (ds_bpermute) and keep the smaller or the larger of the two
-// with one median-of-three against 0 or 0xFFFFFFFF.  No barriers, no atomics.
+// are a min/max pair, exchanges between lanes fetch the partner's word (a DPP
+// move inside a row of 16 lanes where a pattern exists, else the LDS crossbar)
+// and keep the smaller or the larger of the two with one median-of-three
+// against 0 or 0xFFFFFFFF.  No barriers, no atomics.
 #include "common.h"
 
 namespace gr {
@@ -37,19 +38,31 @@ struct BuildArgs {
     int n_inst, max_entries, max_len;
 };
 
-// (No DPP instruction may read a register this writes within two instructions;
-// this file uses none.)
+// Median of three; the compiler turns this shape into one v_med3_u32.
 __device__ __forceinline__ uint32_t med3_u32(uint32_t a, uint32_t b, uint32_t c)
 {
-    uint32_t o;
-    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(o) : "v"(a), "v"(b), "v"(c));
-    return o;
+    return min(max(a, b), max(min(a, b), c));
 }
 
-// The partner lane's copy of x; lane4 = 4 * lane, mask = lane XOR distance.
+template <int kCtrl>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t x)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, kCtrl, 0xf, 0xf, false);
+}
+
+// The copy of x held by lane (lane ^ mask); lane4 = 4 * lane.  Partners inside a
+// row of 16 lanes that a DPP pattern reaches come straight from the register
+// file; the others through the LDS crossbar.
 __device__ __forceinline__ uint32_t fetch_xor(uint32_t x, int mask, int lane4)
 {
-    return (uint32_t)__builtin_amdgcn_ds_bpermute(lane4 ^ (mask << 2), (int)x);
+    switch (mask) {
+        case 1: return dpp_move<0xB1>(x);      // quad_perm [1,0,3,2]
+        case 2: return dpp_move<0x4E>(x);      // quad_perm [2,3,0,1]
+        case 3: return dpp_move<0x1B>(x);      // quad_perm [3,2,1,0]
+        case 7: return dpp_move<0x141>(x);     // row_half_mirror
+        case 15: return dpp_move<0x140>(x);    // row_mirror
+        default: return (uint32_t)__builtin_amdgcn_ds_bpermute(lane4 ^ (mask << 2), (int)x);
+    }
 }
 
 __device__ __forceinline__ void order2(uint32_t& lo, uint32_t& hi)
