@@ -43,8 +43,8 @@ def _load():
         lib.gro_free.argtypes = [p]
         lib.gro_status.argtypes = [p, p, p, p]
         lib.gro_step_table.argtypes = [p, C.c_int32, p]
-        lib.gro_pair_T.argtypes = [p, C.c_int64, p, p, p]
-        lib.gro_route.argtypes = [p, C.c_int64] + [p] * 8
+        lib.gro_pair_T.argtypes = [p, C.c_int64] + [p] * 6
+        lib.gro_route.argtypes = [p, C.c_int64] + [p] * 11
         lib.gro_threads.restype = C.c_int32
         _lib = lib
     return _lib
@@ -116,19 +116,29 @@ class SimulatedFleet:
         _load().gro_step_table(self._h, int(g), _ptr(w))
         return w
 
-    def pair_T(self, c0, length) -> np.ndarray:
+    @staticmethod
+    def _hits(hits):
+        """hits: None or (hit_off[n+1], hit_inst, hit_len): cached prefixes by request (Eq. 2's H)."""
+        if hits is None:
+            return None, None, None
+        return tuple(_i32(a) for a in hits)
+
+    def pair_T(self, c0, length, hits=None) -> np.ndarray:
         c0, length = _i32(c0), _i32(length)
+        ho, hi, hl = self._hits(hits)
         out = np.zeros((len(c0), self.n_inst), dtype=np.float64)
-        _load().gro_pair_T(self._h, len(c0), _ptr(c0), _ptr(length), _ptr(out))
+        _load().gro_pair_T(self._h, len(c0), _ptr(c0), _ptr(length), _ptr(ho), _ptr(hi), _ptr(hl), _ptr(out))
         return out
 
-    def route(self, c0, length, deadline, exclude=None) -> Routing:
+    def route(self, c0, length, deadline, exclude=None, hits=None) -> Routing:
         c0, length, deadline = _i32(c0), _i32(length), _f64(deadline)
         n = len(c0)
         ex = None if exclude is None else _i32(exclude)
+        ho, hi, hl = self._hits(hits)
         r = Routing(np.zeros(n, np.int32), np.zeros(n, np.float64),
                     np.zeros(n, np.uint8), np.zeros(n, np.float64))
         _load().gro_route(self._h, n, _ptr(c0), _ptr(length), _ptr(deadline), _ptr(ex),
+                          _ptr(ho), _ptr(hi), _ptr(hl),
                           _ptr(r.inst), _ptr(r.slack), _ptr(r.fallback), _ptr(r.T))
         return r
 

@@ -210,14 +210,16 @@ void gro_step_table(const gro_fleet *f, int32_t g, double *w)
 }
 
 /*
- * Eq. 2 for one (request, instance) pair.  The request waits q_g, prefills
- * its own c0 tokens (H = 0 cached), then takes len decode steps in a batch
- * that holds it and whoever of the instance's requests is still running: the
- * first len step times of the instance, plus what its own presence adds to
- * each of them (one more batch member, its context c0 + s - 1 at step s).
- * Past the instance's last request only the new request is left.
+ * Eq. 2 for one (request, instance) pair.  The request waits q_g, prefills the
+ * part of its c0 tokens that is not already cached on the instance (H of them
+ * are: Eq. 2's "hit prefix token length"), then takes len decode steps in a
+ * batch that holds it and whoever of the instance's requests is still running:
+ * the first len step times of the instance, plus what its own presence adds to
+ * each of them (one more batch member, its context c0 + s - 1 at step s: cached
+ * tokens are still context).  Past the instance's last request only the new
+ * request is left.
  */
-static double pair_T(const gro_fleet *f, int32_t g, int64_t c0, int64_t len)
+static double pair_T(const gro_fleet *f, int32_t g, int64_t c0, int64_t len, int64_t hit)
 {
     int c = f->inst_class[g];
     double alpha = f->alpha[c], beta = f->beta[c], gamma = f->gamma[c], delta = f->delta[c];
@@ -226,26 +228,46 @@ static double pair_T(const gro_fleet *f, int32_t g, int64_t c0, int64_t len)
                                 : f->w[g][smax] + (double)(len - smax) * alpha;
     double tri = (double)(len * (len - 1) / 2);
     double own = beta * (double)len + gamma * ((double)(c0 * len) + tri);
-    return f->q[g] + delta * (double)c0 + base + own;
+    return f->q[g] + delta * (double)(c0 - hit) + base + own;
 }
 
-/* T for every pair: out[r * n_inst + g] */
+/*
+ * Reusable prefix of request r on instance g: the hits of request r are
+ * entries hit_off[r] .. hit_off[r+1]-1 of (hit_inst, hit_len).  No entry: 0.
+ * Should an instance be named twice the longer prefix counts; a prefix is
+ * never longer than the request's tokens nor negative.
+ */
+static int64_t reusable_prefix(const int32_t *hit_off, const int32_t *hit_inst, const int32_t *hit_len,
+                               int64_t r, int32_t g, int64_t c0)
+{
+    if (!hit_off) return 0;
+    int64_t h = 0;
+    for (int32_t k = hit_off[r]; k < hit_off[r + 1]; ++k)
+        if (hit_inst[k] == g && hit_len[k] > h) h = hit_len[k];
+    return h > c0 ? c0 : h;
+}
+
+/* T for every pair: out[r * n_inst + g]; hit_off may be NULL (no cached prefixes) */
 void gro_pair_T(const gro_fleet *f, int64_t n_req, const int32_t *c0, const int32_t *len,
+                const int32_t *hit_off, const int32_t *hit_inst, const int32_t *hit_len,
                 double *out)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t r = 0; r < n_req; ++r)
         for (int32_t g = 0; g < f->n_inst; ++g)
-            out[r * f->n_inst + g] = pair_T(f, g, c0[r], len[r]);
+            out[r * f->n_inst + g] =
+                pair_T(f, g, c0[r], len[r], reusable_prefix(hit_off, hit_inst, hit_len, r, g, c0[r]));
 }
 
 /*
  * Alg. 1 for a batch, every request against the same snapshot of the fleet.
  * exclude (may be NULL) names an instance a request may not be sent to
- * (-1: none).  out_inst = -1 when no instance is allowed at all.
+ * (-1: none).  hit_off (may be NULL) lists cached prefixes, see above.
+ * out_inst = -1 when no instance is allowed at all.
  */
 void gro_route(const gro_fleet *f, int64_t n_req, const int32_t *c0, const int32_t *len,
                const double *deadline, const int32_t *exclude,
+               const int32_t *hit_off, const int32_t *hit_inst, const int32_t *hit_len,
                int32_t *out_inst, double *out_slack, uint8_t *out_fallback, double *out_T)
 {
 #pragma omp parallel for schedule(static)
@@ -256,7 +278,8 @@ void gro_route(const gro_fleet *f, int64_t n_req, const int32_t *c0, const int32
         double best_feas_d = 0.0, best_feas_T = 0.0, best_any_T = 0.0;
         for (int32_t g = 0; g < f->n_inst; ++g) {
             if (g == ex) continue;
-            double T = pair_T(f, g, c0[r], len[r]);
+            double T = pair_T(f, g, c0[r], len[r],
+                              reusable_prefix(hit_off, hit_inst, hit_len, r, g, c0[r]));
             if (T <= D) {
                 if (best_feas < 0 || f->d[g] > best_feas_d) {
                     best_feas = g; best_feas_d = f->d[g]; best_feas_T = T;

@@ -11,15 +11,18 @@ from __future__ import annotations
 
 def replay(coef, active, queued):
     """coef = (delta, alpha, beta, gamma); active = [(prompt, gen, rem)];
-    queued = [(prompt, len)].  Returns (q, first_step, finish list in the
-    order actives then queued)."""
+    queued = [(prompt, len)] or [(prompt, len, cached)]: `cached` tokens of the
+    prompt need no prefill (Eq. 2's hit prefix) but count as context.  Returns
+    (q, first_step, finish list in the order actives then queued)."""
     delta, alpha, beta, gamma = coef
     t = 0.0
     batch = []
     for i, (p, g, r) in enumerate(active):
         batch.append({"id": i, "rem": r, "ctx": p + g})
-    for j, (p, l) in enumerate(queued):
-        t += delta * p
+    for j, entry in enumerate(queued):
+        p, l = entry[0], entry[1]
+        cached = entry[2] if len(entry) > 2 else 0
+        t += delta * (p - cached)
         batch.append({"id": len(active) + j, "rem": l, "ctx": p})
     q = t
     finish = [None] * len(batch)
@@ -35,9 +38,10 @@ def replay(coef, active, queued):
     return q, first, finish
 
 
-def latency_if_routed(coef, active, queued, c0, length):
-    """T(r, g) by definition: append r behind the queue and replay."""
-    _, _, finish = replay(coef, active, list(queued) + [(c0, length)])
+def latency_if_routed(coef, active, queued, c0, length, cached=0):
+    """T(r, g) by definition: append r behind the queue and replay; `cached`
+    of its c0 tokens are already on the instance."""
+    _, _, finish = replay(coef, active, list(queued) + [(c0, length, cached)])
     return finish[-1]
 
 

@@ -150,6 +150,84 @@ def test_risk_scan_matches_brute_force():
             i += 1
 
 
+# --------------------------------------------------------------------------- cached prefixes (Eq. 2's H)
+def random_hits(rng, n_req, n_inst, c0, density=0.5):
+    """CSR (hit_off, hit_inst, hit_len): each request has a cached prefix on a random subset of instances."""
+    off, inst, ln = [0], [], []
+    for r in range(n_req):
+        gs = [g for g in range(n_inst) if rng.random() < density]
+        for g in gs:
+            inst.append(g)
+            ln.append(int(rng.integers(1, int(c0[r]) + 1)))
+        off.append(len(inst))
+    return (np.array(off, np.int32), np.array(inst, np.int32), np.array(ln, np.int32))
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_cached_prefix_matches_brute_force_replay(seed):
+    """Eq. 2: the cached part of the prompt is not prefilled.  The brute force
+    replays the instance with the request appended, charging prefill for the
+    uncached tokens only and carrying all tokens as context."""
+    rng = np.random.default_rng(300 + seed)
+    coefs, inst_class, actives, queued = random_tiny(rng, n_inst=4)
+    f = make(coefs, inst_class, actives, queued)
+    sim = oracle.simulate(f)
+    n = 30
+    c0 = rng.integers(1, 60, n)
+    ln = rng.integers(1, 31, n)
+    hits = random_hits(rng, n, 4, c0)
+    T = sim.pair_T(c0, ln, hits=hits)
+    T0 = sim.pair_T(c0, ln)
+    H = np.zeros((n, 4), dtype=np.int64)
+    for r in range(n):
+        for k in range(hits[0][r], hits[0][r + 1]):
+            H[r, hits[1][k]] = hits[2][k]
+    want = np.array([[brute.latency_if_routed(coefs[inst_class[g]], actives[g], queued[g],
+                                              int(c0[r]), int(ln[r]), int(H[r, g])) for g in range(4)]
+                     for r in range(n)])
+    np.testing.assert_allclose(T, want, rtol=1e-11)
+    # closed form of the difference: exactly the prefill of the cached tokens
+    delta = np.array([coefs[c][0] for c in inst_class])
+    np.testing.assert_allclose(T0 - T, H * delta[None, :], rtol=1e-9, atol=1e-12)
+    assert (H > 0).any() and (H == 0).any()
+    # selection with hits against the brute force's Alg. 1
+    d = [brute.replay(coefs[inst_class[g]], actives[g], queued[g])[1] for g in range(4)]
+    D = want.min(axis=1) * rng.uniform(0.5, 2.5, n)
+    ex = rng.integers(-1, 4, n).astype(np.int32)
+    got = sim.route(c0, ln, D, exclude=ex, hits=hits)
+    for r in range(n):
+        pick, fb = brute.select(list(want[r]), d, D[r], int(ex[r]))
+        assert got.inst[r] == pick and bool(got.fallback[r]) == fb
+        assert got.slack[r] == pytest.approx(D[r] - want[r, pick], rel=1e-9, abs=1e-12)
+
+
+def test_cached_prefix_special_cases():
+    rng = np.random.default_rng(7)
+    coefs, inst_class, actives, queued = random_tiny(rng, n_inst=3)
+    f = make(coefs, inst_class, actives, queued)
+    sim = oracle.simulate(f)
+    c0, ln = np.array([40, 40, 40]), np.array([5, 5, 5])
+    base = sim.pair_T(c0, ln)
+    # no entries, zero-length entries: nothing changes
+    empty = (np.zeros(4, np.int32), np.zeros(0, np.int32), np.zeros(0, np.int32))
+    assert np.array_equal(sim.pair_T(c0, ln, hits=empty), base)
+    zero = (np.array([0, 1, 2, 3], np.int32), np.array([0, 1, 2], np.int32), np.zeros(3, np.int32))
+    assert np.array_equal(sim.pair_T(c0, ln, hits=zero), base)
+    # a prefix longer than the request is cut to the request; the whole prompt cached = no prefill at all
+    full = (np.array([0, 1, 2, 3], np.int32), np.array([0, 1, 2], np.int32), np.array([40, 1000, 39], np.int32))
+    T = sim.pair_T(c0, ln, hits=full)
+    delta = np.array([coefs[c][0] for c in inst_class])
+    assert T[0, 0] == pytest.approx(base[0, 0] - 40 * delta[0], rel=1e-12)
+    assert T[1, 1] == pytest.approx(base[1, 1] - 40 * delta[1], rel=1e-12)
+    assert T[2, 2] == pytest.approx(base[2, 2] - 39 * delta[2], rel=1e-12)
+    # an instance named twice: the longer prefix counts
+    twice = (np.array([0, 2, 2, 2], np.int32), np.array([1, 1], np.int32), np.array([7, 30], np.int32))
+    assert sim.pair_T(c0, ln, hits=twice)[0, 1] == pytest.approx(base[0, 1] - 30 * delta[1], rel=1e-12)
+    # a hit can only help: it never raises a latency, and a hit on a feasible choice leaves it feasible
+    hits = random_hits(rng, 3, 3, c0, density=1.0)
+    assert np.all(sim.pair_T(c0, ln, hits=hits) <= base)
+
+
 # --------------------------------------------------------------------------- closed forms
 def tri(x):
     return x * (x - 1) / 2
