@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="heavy", help="tiny | mid | large | migrate | heavy")
+    ap.add_argument("--prefixes", type=float, default=0.0,
+                    help="mean number of cached prefixes per incoming request (Eq. 2's H); 0: none")
     ap.add_argument("--cpu-seconds", type=float, default=15.0,
                     help="target CPU time of the reference sample (0: skip)")
     return ap.parse_args()
@@ -143,11 +145,18 @@ def main():
     tsl = torch.empty(na, dtype=torch.float32, device=dev)
     nfl = torch.zeros(1, dtype=torch.int32, device=dev)
 
+    hits = None
+    if a.prefixes > 0 and R:
+        hits = [torch.from_numpy(x).to(dev) for x in workloads.cached_prefixes(fl, a.prefixes, seed=0)]
+
     def step():
         h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"],
                           d["q_off"], d["q_prompt"], d["q_len"], fin)
-        if R:
+        if R and hits is None:
             h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, slack)
+        elif R:
+            h.gr_score_route_cached(d["in_prompt"], d["in_len"], d["in_budget"], hits[0], hits[1], hits[2],
+                                    inst, slack)
         h.gr_risk_scan(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem_refreshed"],
                        d["q_off"], d["q_prompt"], d["q_len"], d["act_budget"],
                        flag, fin2, tgt, tsl, nfl)
@@ -210,7 +219,8 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": a.config, "instances": M, "held_requests": entries,
+        "config": {"workload": a.config if hits is None else f"{a.config}+prefixes({a.prefixes:g}/request)",
+                   "instances": M, "held_requests": entries,
                    "incoming": R, "flagged": n_flagged, "route_pairs": pairs_route,
                    "migration_pairs": pairs_mig},
         "roofline": roofline,

@@ -142,6 +142,30 @@ int gr_score_route(gr_fleet* f, int64_t n_req,
                    float* out_T, void* hip_stream);
 
 /*
+ * Step 2 with cached prefixes (Eq. 2's hit prefix token length H_{r,g};
+ * Alg. 1's prefix-reuse lookup before T(r,g) is formed).  As gr_score_route,
+ * but request r already has hit_len[k] of its ctx0 tokens cached on instance
+ * hit_inst[k] for k = hit_off[r] .. hit_off[r+1]-1; those tokens are not
+ * prefilled again (they still count as context while decoding):
+ *   T(r,g) = q_g + delta*(ctx0 - H_{r,g}) + [decode time as in gr_score_route].
+ * Pairs without an entry have H = 0.  An instance named more than once for a
+ * request counts with its longest prefix; a prefix is cut to [0, ctx0].
+ *
+ *   hit_off    DEVICE int32[n_req+1]  CSR offsets by request, non-decreasing, hit_off[0] = 0
+ *   hit_inst   DEVICE int32[n_hits]   instance of each cached prefix (entries outside [0, n_inst) are ignored)
+ *   hit_len    DEVICE int32[n_hits]   its length in tokens
+ *   n_hits     number of entries (0 allowed: same as gr_score_route)
+ * out_T, when given, holds T with the prefixes applied.
+ */
+int gr_score_route_cached(gr_fleet* f, int64_t n_req,
+                          const int32_t* ctx0, const int32_t* pred_len, const float* budget,
+                          const int32_t* exclude_inst,
+                          const int32_t* hit_off, const int32_t* hit_inst, const int32_t* hit_len,
+                          int64_t n_hits,
+                          int32_t* out_inst, float* out_slack, uint8_t* out_fallback,
+                          float* out_T, void* hip_stream);
+
+/*
  * Step 3 (Sec. 3.4, periodic re-check).  Rebuilds the status from refreshed
  * remaining lengths (as gr_build_status, replacing the handle's tables), flags
  * every active request whose expected finish exceeds its budget

@@ -11,7 +11,8 @@ namespace {
 const char* const kKernelNames[kNumKernels] = {
     "k_build", "k_rank_count", "k_rank_final",
     "k_hist<route>", "k_scan<route>", "k_scatter<route>", "k_memo<route>", "k_tile<route>",
-    "k_hist<migrate>", "k_scan<migrate>", "k_scatter<migrate>", "k_memo<migrate>", "k_tile<migrate>"};
+    "k_hist<migrate>", "k_scan<migrate>", "k_scatter<migrate>", "k_memo<migrate>", "k_tile<migrate>",
+    "k_hits<route>"};
 
 template <typename T>
 bool dev_alloc(T** p, size_t n)
@@ -86,7 +87,7 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         dev_alloc(&f->act_inst, f->max_active) && dev_alloc(&f->counters, 1) &&
         dev_alloc(&f->len_cnt, f->bins) && dev_alloc(&f->len_base, f->bins) &&
         dev_alloc(&f->row_len, f->row_cap) && dev_alloc(&f->row_off, f->row_cap + 1) &&
-        dev_alloc(&f->tile_off, f->row_cap + 1) && dev_alloc(&f->totals, 4) &&
+        dev_alloc(&f->tile_off, f->row_cap + 1) && dev_alloc(&f->len_row, f->bins) && dev_alloc(&f->totals, 4) &&
         dev_alloc(&f->recs, f->req_cap) && dev_alloc(&f->memo, (size_t)f->row_cap * f->m_pad);
     if (!ok) { gr_destroy(f); return GR_ERR_NOMEM; }
 
@@ -115,7 +116,7 @@ int gr_destroy(gr_fleet* f)
     (void)hipDeviceSynchronize();
     void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabGH, f->headGH, f->hN, f->hD, f->rank_acc,
                     f->rank, f->order, f->posK, f->act_inst, f->counters, f->len_cnt, f->len_base, f->row_len,
-                    f->row_off, f->tile_off, f->totals, f->recs, f->memo};
+                    f->row_off, f->tile_off, f->len_row, f->totals, f->recs, f->memo};
     int rc = GR_OK;
     for (void* p : ptrs)
         if (p && hipFree(p) != hipSuccess) rc = GR_ERR_HIP;
@@ -159,6 +160,25 @@ int gr_score_route(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_
     ScoreOut o{};
     o.inst = out_inst; o.slack = out_slack; o.fallback = out_fallback; o.T = out_T;
     return launch_score(f, src, false, o, static_cast<hipStream_t>(hip_stream));
+}
+
+int gr_score_route_cached(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_t* pred_len,
+                          const float* budget, const int32_t* exclude_inst,
+                          const int32_t* hit_off, const int32_t* hit_inst, const int32_t* hit_len,
+                          int64_t n_hits, int32_t* out_inst, float* out_slack, uint8_t* out_fallback,
+                          float* out_T, void* hip_stream)
+{
+    if (n_hits < 0 || (n_req > 0 && !hit_off) || (n_hits > 0 && (!hit_inst || !hit_len)))
+        return GR_ERR_INVALID_ARG;
+    const int rc = gr_score_route(f, n_req, ctx0, pred_len, budget, exclude_inst, out_inst, out_slack,
+                                  out_fallback, out_T, hip_stream);
+    if (rc != GR_OK || n_req == 0) return rc;
+    ReqSrc src{};
+    src.ctx0 = ctx0; src.pred_len = pred_len; src.budget = budget; src.exclude = exclude_inst;
+    src.n = n_req;
+    ScoreOut o{};
+    o.inst = out_inst; o.slack = out_slack; o.fallback = out_fallback; o.T = out_T;
+    return launch_hits(f, src, hit_off, hit_inst, hit_len, n_hits, o, static_cast<hipStream_t>(hip_stream));
 }
 
 int gr_risk_scan(gr_fleet* f, const int32_t* act_off, const int32_t* act_prompt,

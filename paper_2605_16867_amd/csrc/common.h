@@ -76,7 +76,7 @@ struct ScoreOut {
 
 enum KernelId {
     kBuild = 0, kRankCount, kRankFinal, kHistRoute, kScanRoute, kScatterRoute, kMemoRoute, kTileRoute,
-    kHistMigrate, kScanMigrate, kScatterMigrate, kMemoMigrate, kTileMigrate, kNumKernels
+    kHistMigrate, kScanMigrate, kScatterMigrate, kMemoMigrate, kTileMigrate, kHitsRoute, kNumKernels
 };
 
 struct Profiler {
@@ -122,6 +122,7 @@ struct gr_fleet {
     int* row_len = nullptr;   // [row_cap] the distinct lengths, ascending
     int* row_off = nullptr;   // [row_cap+1] first request of each distinct length
     int* tile_off = nullptr;  // [row_cap+1] first tile of each distinct length
+    int* len_row = nullptr;   // [bins] row of each length present in the last batch
     int* totals = nullptr;    // [4] requests, distinct lengths, tiles
     gr::ReqRec* recs = nullptr;  // [req_cap] requests in grouped order
     float* memo = nullptr;       // [row_cap][m_pad] E per distinct length and position
@@ -165,6 +166,8 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s);
 size_t score_lds_bytes(const gr_fleet* f);
 int score_prepare(gr_fleet* f);
 int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& out, hipStream_t s);
+int launch_hits(gr_fleet* f, const ReqSrc& src, const int* hit_off, const int* hit_inst, const int* hit_len,
+                int64_t n_hits, const ScoreOut& out, hipStream_t s);
 
 // ------------------------------------------------------------------ wave helpers
 __device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }

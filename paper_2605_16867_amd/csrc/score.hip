@@ -85,13 +85,14 @@ __device__ inline unsigned long long block_incl_scan(unsigned long long v, unsig
 
 // One workgroup walks the length histogram (copied to LDS; a thread owns a run
 // of consecutive lengths): the first slot of each length in grouped order, the
-// list of lengths present ("rows"), the first tile of each row (a tile = up to
-// kTileReq requests of one length), and the totals.  The histogram is cleared
+// list of lengths present ("rows") and the row of each such length, the first
+// tile of each row (a tile = up to kTileReq requests of one length), and the
+// totals.  The histogram is cleared
 // for the next call.
 __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, int* __restrict__ len_base,
                                                      int* __restrict__ row_len, int* __restrict__ row_off,
-                                                     int* __restrict__ tile_off, int* __restrict__ totals,
-                                                     int* __restrict__ out_n, int bins)
+                                                     int* __restrict__ tile_off, int* __restrict__ len_row,
+                                                     int* __restrict__ totals, int* __restrict__ out_n, int bins)
 {
     extern __shared__ uint32_t lds[];
     int* cnt = reinterpret_cast<int*>(lds);
@@ -114,6 +115,7 @@ __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, 
         const unsigned c = (unsigned)cnt[i];
         cnt[i] = (int)(run & 0xFFFFFFFFull);
         if (c) {
+            len_row[i] = u;
             row_len[u] = i;
             row_off[u] = (int)(run & 0xFFFFFFFFull);
             tile_off[u] = (int)(run >> 32);
@@ -713,6 +715,76 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
     }
 }
 
+// ------------------------------------------------------------------ cached prefixes
+struct HitArgs {
+    const int *ctx0, *pred_len;
+    const float* budget;
+    const int* exclude;
+    const int *hit_off, *hit_inst, *hit_len;
+    const int *len_row, *rank, *order;
+    const float* memo;
+    const float2* posK;
+    int* out_inst;
+    float* out_slack;
+    uint8_t* out_fallback;
+    float* out_T;
+    int64_t n, n_hits;
+    int n_inst, m_pad, max_len;
+};
+
+// Eq. 2's hit prefix H_{r,g}, after the pass without it: a cached prefix of h
+// tokens on instance g takes delta_g * h off T(r,g) and changes nothing else,
+// so Alg. 1's answer can only move to an instance the request has a prefix on.
+// One thread per request that has any: the choice made without prefixes
+// against the request's own short list.  Feasible set: the earlier position in
+// capability order wins; otherwise the smallest T, ties to the lowest index
+// (the minimum over all instances is either the old one or among the hits,
+// because a hit only lowers its own pair).
+__global__ __launch_bounds__(kBlock) void k_hits(HitArgs a)
+{
+    const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r >= a.n) return;
+    const int64_t h0 = min(max((int64_t)a.hit_off[r], (int64_t)0), a.n_hits);
+    const int64_t h1 = min(max((int64_t)a.hit_off[r + 1], h0), a.n_hits);
+    if (h0 >= h1) return;
+    const int L = min(max(a.pred_len[r], 0), a.max_len);
+    const int ci = a.ctx0[r];
+    const float c0 = (float)ci, Lf = (float)L, D = a.budget[r];
+    const float Dc = D > FLT_MAX ? FLT_MAX : D;
+    const int ex = a.exclude ? a.exclude[r] : -1;
+    const float* __restrict__ rowE = a.memo + (size_t)a.len_row[L] * a.m_pad;
+
+    int feasP = 0x7fffffff, anyG = -1;
+    float feasT = 0.f, anyT = __builtin_inff();
+    const int g0 = a.out_inst[r];
+    if (g0 >= 0) {
+        const int p0 = a.rank[g0];
+        const float T0 = fmaf(c0, kappa_of(a.posK[p0], Lf), rowE[p0]);
+        if (T0 <= Dc) { feasP = p0; feasT = T0; }
+        anyG = g0; anyT = T0;
+    }
+    for (int64_t k = h0; k < h1; ++k) {
+        const int g = a.hit_inst[k];
+        if (g < 0 || g >= a.n_inst) continue;
+        const int h = min(max(a.hit_len[k], 0), max(ci, 0));
+        const int p = a.rank[g];
+        const float2 dg = a.posK[p];
+        const float T = fmaf(-(float)h, dg.x, fmaf(c0, kappa_of(dg, Lf), rowE[p]));
+        if (a.out_T) {          // (an instance named twice: the longer prefix, i.e. the smaller T, stays)
+            float* t = a.out_T + (size_t)r * a.n_inst + g;
+            *t = fminf(*t, T);
+        }
+        if (g == ex) continue;
+        if (T <= Dc && (p < feasP || (p == feasP && T < feasT))) { feasP = p; feasT = T; }
+        if (T < anyT || (T == anyT && g < anyG)) { anyT = T; anyG = g; }
+    }
+    const bool found = feasP != 0x7fffffff;
+    const int g = found ? a.order[feasP] : anyG;
+    a.out_inst[r] = g;
+    a.out_slack[r] = g >= 0 ? D - (found ? feasT : anyT) : 0.f;
+    if (a.out_fallback) a.out_fallback[r] = !found;
+}
+
 __global__ void k_set_int(int* p, int v) { *p = v; }
 
 template <typename K>
@@ -760,7 +832,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     {
         ProfScope ps(f, kScanRoute + off, s);
         hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanBlock), scat_lds, s, f->len_cnt, f->len_base, f->row_len,
-                           f->row_off, f->tile_off, f->totals, out.n_selected, bins);
+                           f->row_off, f->tile_off, f->len_row, f->totals, out.n_selected, bins);
     }
     {
         ProfScope ps(f, kScatterRoute + off, s);
@@ -797,6 +869,21 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         if (out.T) hipLaunchKernelGGL(k_tile<true>, dim3(blocks), dim3(kBlock), 0, s, t);
         else hipLaunchKernelGGL(k_tile<false>, dim3(blocks), dim3(kBlock), 0, s, t);
     }
+    return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
+}
+
+int launch_hits(gr_fleet* f, const ReqSrc& src, const int* hit_off, const int* hit_inst, const int* hit_len,
+                int64_t n_hits, const ScoreOut& out, hipStream_t s)
+{
+    if (src.n == 0 || n_hits == 0) return GR_OK;
+    HitArgs h{};
+    h.ctx0 = src.ctx0; h.pred_len = src.pred_len; h.budget = src.budget; h.exclude = src.exclude;
+    h.hit_off = hit_off; h.hit_inst = hit_inst; h.hit_len = hit_len;
+    h.len_row = f->len_row; h.rank = f->rank; h.order = f->order; h.memo = f->memo; h.posK = f->posK;
+    h.out_inst = out.inst; h.out_slack = out.slack; h.out_fallback = out.fallback; h.out_T = out.T;
+    h.n = src.n; h.n_hits = n_hits; h.n_inst = f->n_inst; h.m_pad = f->m_pad; h.max_len = f->max_len;
+    ProfScope ps(f, kHitsRoute, s);
+    hipLaunchKernelGGL(k_hits, dim3((unsigned)((src.n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, h);
     return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
 }
 

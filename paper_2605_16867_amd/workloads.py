@@ -203,3 +203,26 @@ def make_fleet(spec: FleetSpec) -> Fleet:
         q_off=q_off, q_prompt=qp, q_len=ql,
         in_prompt=in_prompt, in_len=in_len, in_budget=in_budget,
     )
+
+
+def cached_prefixes(fl: Fleet, mean_hits: float = 2.0, seed: int = 0):
+    """Cached prompt prefixes of the incoming requests, as Eq. 2's H_{r,g}: a
+    CSR (hit_off[R+1], hit_inst, hit_len).  Each request has a prefix on a
+    Poisson(mean_hits) number of distinct instances (agentic sessions return
+    to instances that served their earlier turns), of a length uniform in
+    [1, prompt].  Draw order: counts, instances, lengths."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    R, M = len(fl.in_prompt), fl.n_inst
+    cnt = np.minimum(rng.poisson(mean_hits, R), M).astype(np.int64)
+    off = np.zeros(R + 1, dtype=np.int32)
+    off[1:] = np.cumsum(cnt)
+    n = int(off[-1])
+    owner = np.repeat(np.arange(R), cnt)
+    # distinct instances per request: a random start and a stride coprime to M walk M distinct values
+    start = rng.integers(0, M, R)
+    stride = 2 * rng.integers(0, max(M // 2, 1), R) + 1 if M % 2 == 0 else np.ones(R, dtype=np.int64)
+    k = np.arange(n) - off[owner]
+    inst = ((start[owner] + k * stride[owner]) % M).astype(np.int32)
+    frac = rng.uniform(0.0, 1.0, n)
+    ln = np.maximum(1, np.ceil(frac * fl.in_prompt[owner])).astype(np.int32)
+    return off, inst, ln

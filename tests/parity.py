@@ -104,6 +104,17 @@ def upload(fl, device="cuda:0"):
              "q_off", "q_prompt", "q_len", "in_prompt", "in_len", "in_budget")}
 
 
+def sub_csr(hits, idx):
+    """The hit lists of the requests idx, as a CSR of their own."""
+    off, inst, ln = (np.asarray(x) for x in hits)
+    cnt = (off[1:] - off[:-1])[idx]
+    new_off = np.zeros(len(idx) + 1, dtype=np.int32)
+    new_off[1:] = np.cumsum(cnt)
+    take = np.concatenate([np.arange(off[i], off[i + 1]) for i in idx]) if len(idx) else np.zeros(0, np.int64)
+    take = take.astype(np.int64)
+    return new_off, inst[take].astype(np.int32), ln[take].astype(np.int32)
+
+
 def max_len_of(fl) -> int:
     return int(fl.max_len) if hasattr(fl, "max_len") else int(fl.spec.max_len)
 
@@ -117,9 +128,11 @@ def make_handle(fl, max_requests: Optional[int] = None, max_entries: Optional[in
 
 
 def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit: int = 1 << 25,
-                  exclude=None):
+                  exclude=None, hits=None):
     """Run the whole path on the GPU and check it.  ``sample``: number of
-    requests (and of active requests) checked against the reference; None = all."""
+    requests (and of active requests) checked against the reference; None = all.
+    ``hits``: (hit_off, hit_inst, hit_len) cached prefixes of the incoming requests
+    (routes through gr_score_route_cached)."""
     import torch
     dev = "cuda:0"
     rep = {}
@@ -155,12 +168,18 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
         fb = torch.zeros(R, dtype=torch.uint8, device=dev)
         want_T = R * M <= full_T_limit
         outT = torch.zeros(R * M, dtype=torch.float32, device=dev) if want_T else None
-        h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, slack,
-                         exclude_inst=None if ex_np is None else torch.from_numpy(ex_np).to(dev),
-                         out_fallback=fb, out_T=outT)
+        ex_t = None if ex_np is None else torch.from_numpy(ex_np).to(dev)
+        if hits is None:
+            h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, slack,
+                             exclude_inst=ex_t, out_fallback=fb, out_T=outT)
+        else:
+            ht = [torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev) for x in hits]
+            h.gr_score_route_cached(d["in_prompt"], d["in_len"], d["in_budget"], ht[0], ht[1], ht[2],
+                                    inst, slack, exclude_inst=ex_t, out_fallback=fb, out_T=outT)
         torch.cuda.synchronize()
         idx = np.arange(R) if sample is None or sample >= R else np.sort(rng.choice(R, sample, replace=False))
-        T = sim.pair_T(fl.in_prompt[idx], fl.in_len[idx])
+        sub_hits = None if hits is None else sub_csr(hits, idx)
+        T = sim.pair_T(fl.in_prompt[idx], fl.in_len[idx], hits=sub_hits)
         D = fl.in_budget[idx].astype(np.float64)
         if want_T:
             e = rel_err(outT.cpu().numpy().reshape(R, M)[idx], T)
@@ -170,7 +189,10 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
         want = check_choices("route", T, D, sim.rank, None if ex_np is None else ex_np[idx], picked,
                              slack.cpu().numpy()[idx], rep, fallback=fb.cpu().numpy()[idx])
         ref = sim.route(fl.in_prompt[idx], fl.in_len[idx], D,
-                        exclude=None if ex_np is None else ex_np[idx])
+                        exclude=None if ex_np is None else ex_np[idx], hits=sub_hits)
+        if hits is not None:
+            rep["route_moved_by_hits"] = int((ref.inst != sim.route(
+                fl.in_prompt[idx], fl.in_len[idx], D, exclude=None if ex_np is None else ex_np[idx]).inst).sum())
         assert np.array_equal(ref.inst, want), "reference scan and classifier disagree"
 
     # ---- step 3: risk scan

@@ -221,3 +221,55 @@ def test_zero_requests_and_zero_actives():
     want = 1e9 - (1e-5 * 7 + 3 * (0.01 + 1e-4) + 1e-8 * (7 * 3 + 3))
     assert abs(sl[0].item() - want) <= 1e-4 * 1e9
     h.close()
+
+
+def test_cached_prefix_edge_cases():
+    """Empty hit lists, zero-length and over-long prefixes, an instance named twice, ids out of
+    range, a prefix on the excluded instance, a prefix that makes an infeasible instance feasible."""
+    rng = np.random.default_rng(12)
+    M = 9
+    acts = [rand_entries(rng, int(n)) for n in rng.integers(50, 300, M)]
+    n = 600
+    inc = np.stack([rng.integers(128, 2049, n), rng.integers(1, 4097, n)], 1)
+    fl = fleet(rng.integers(0, 3, M), acts, [[]] * M, inc, rng.uniform(0.8, 6, n) * solo(inc[:, 0], inc[:, 1]))
+    off, inst, ln = [0], [], []
+    for r in range(n):
+        kind = r % 6
+        if kind == 1:
+            inst += [r % M]; ln += [0]
+        elif kind == 2:
+            inst += [r % M]; ln += [10 ** 6]
+        elif kind == 3:
+            inst += [r % M, r % M]; ln += [5, int(inc[r, 0])]
+        elif kind == 4:
+            inst += [-3, M, (r + 1) % M]; ln += [50, 50, 50]
+        elif kind == 5:
+            inst += list(range(M)); ln += [int(x) for x in rng.integers(1, inc[r, 0] + 1, M)]
+        off.append(len(inst))
+    hits = (np.array(off, np.int32), np.array(inst, np.int32), np.array(ln, np.int32))
+    ex = np.where(np.arange(n) % 2 == 0, -1, np.arange(n) % M).astype(np.int32)
+    # the reference ignores ids out of range as well: it never asks for them
+    parity.run_and_check(fl, hits=hits)
+    parity.run_and_check(fl, exclude=ex, hits=hits)
+    none = (np.zeros(n + 1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.int32))
+    rep = parity.run_and_check(fl, hits=none)
+    assert rep["route_moved_by_hits"] == 0
+
+
+def test_cached_prefixes_decide_when_prefill_dominates():
+    """Slow prefill (delta 200x the usual), short decodes: most of T is prefill, so a cached
+    prefix changes which instances are feasible and which is the least late."""
+    rng = np.random.default_rng(13)
+    slow_prefill = [(4e-3, 0.012, 2e-4, 2e-8), (1e-2, 0.025, 4e-4, 5e-8), (2.4e-2, 0.05, 8e-4, 1e-7)]
+    M = 24
+    acts = [rand_entries(rng, int(k), max_len=64) for k in rng.integers(5, 60, M)]
+    n = 3000
+    inc = np.stack([rng.integers(128, 2049, n), rng.integers(1, 33, n)], 1)
+    fl = fleet(rng.integers(0, 3, M), acts, [[]] * M, inc,
+               rng.uniform(0.5, 3.0, n) * solo(inc[:, 0], inc[:, 1], slow_prefill[0]), classes=slow_prefill)
+    hits = workloads.cached_prefixes(SimpleNamespace(in_prompt=fl.in_prompt, n_inst=M), mean_hits=3.0, seed=5)
+    rep = parity.run_and_check(fl, hits=hits)
+    assert rep["route_moved_by_hits"] > n // 10
+    ex = rng.integers(-1, M, n).astype(np.int32)
+    rep = parity.run_and_check(fl, exclude=ex, hits=hits)
+    assert rep["route_moved_by_hits"] > n // 10

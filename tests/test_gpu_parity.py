@@ -77,3 +77,37 @@ def test_heavy_fleet_loose_slo():
     rep = parity.run_and_check(fl, sample=2048)
     report("heavy x16", rep)
     assert rep["route_feasible_frac"] > 0.3
+
+
+# --------------------------------------------------------------------------- cached prefixes (Eq. 2's H)
+@pytest.mark.parametrize("scale", [1.0, 2.0, 8.0])
+def test_mid_fleet_with_cached_prefixes(scale):
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=scale, occupancy_jitter=True, seed=21))
+    hits = workloads.cached_prefixes(fl, mean_hits=3.0, seed=1)
+    rep = parity.run_and_check(fl, hits=hits)
+    report(f"mid x{scale} + prefixes", rep)
+
+
+def test_cached_prefixes_with_exclusions():
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=2.0, seed=22))
+    hits = workloads.cached_prefixes(fl, mean_hits=4.0, seed=2)
+    rng = np.random.default_rng(3)
+    # half of the requests are barred from an instance they have a prefix on
+    ex = np.full(len(fl.in_prompt), -1, dtype=np.int32)
+    has = np.flatnonzero(np.diff(hits[0]) > 0)
+    pick = has[rng.random(len(has)) < 0.5]
+    ex[pick] = hits[1][hits[0][pick]]
+    report("prefixes + exclude", parity.run_and_check(fl, exclude=ex, hits=hits))
+
+
+def test_large_fleet_with_cached_prefixes_sampled():
+    fl = workloads.make_fleet(workloads.spec("large", slo_scale=3.0, seed=23))
+    hits = workloads.cached_prefixes(fl, mean_hits=2.0, seed=3)
+    report("large x3 + prefixes", parity.run_and_check(fl, sample=4096, hits=hits))
+
+
+def test_heavy_fleet_with_cached_prefixes_sampled():
+    fl = workloads.make_fleet(workloads.spec("heavy"))
+    hits = workloads.cached_prefixes(fl, mean_hits=2.0, seed=4)
+    rep = parity.run_and_check(fl, sample=2048, hits=hits)
+    report("heavy + prefixes", rep)
