@@ -182,3 +182,6 @@ def risk_scan(fleet, act_rem_refreshed, act_budget, only: Optional[np.ndarray] =
         target[idx] = r.inst
         tslack[idx] = r.slack
     return RiskScan(sim, sim.act_finish, flag, target, tslack)
+
+
+from .blackbox import BlendedFleet, SmoothedStatus  # noqa: E402,F401

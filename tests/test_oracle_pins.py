@@ -441,3 +441,82 @@ def test_empty_fleet_pieces():
     one = make([coef], [0], [[(10, 0, 2)]], [[]])
     r = oracle.simulate(one).route([5], [5], [1.0], exclude=[0])
     assert r.inst[0] == -1
+
+
+# --------------------------------------------------------------------------- EMA-smoothed black-box status (Sec. 3.3, Alg. 1)
+def test_ema_closed_form_and_limits():
+    """q_n = (1-a)^n w_0 + a * sum_k (1-a)^(n-k) w_k for the update q <- a*w + (1-a)*q of Alg. 1."""
+    from oracle import blackbox
+    rng = np.random.default_rng(0)
+    w = rng.uniform(0.1, 5.0, (7, 3))
+    for a in (0.0, 0.2, 0.5, 0.9, 1.0):
+        st = blackbox.SmoothedStatus()
+        for k in range(7):
+            st.observe(a, wait=w[k], decode=2 * w[k])
+        n = 6
+        want = (1 - a) ** n * w[0] + a * sum((1 - a) ** (n - k) * w[k] for k in range(1, 7))
+        np.testing.assert_allclose(st.q, want, rtol=1e-13)
+        np.testing.assert_allclose(st.d, 2 * want, rtol=1e-13)
+        assert st.p is None                       # never observed
+    st = blackbox.SmoothedStatus()
+    for k in range(5):
+        st.observe(1.0, wait=w[k])
+    assert np.array_equal(st.q, w[4])             # weight 1: the latest sample
+    st = blackbox.SmoothedStatus()
+    for k in range(5):
+        st.observe(0.3, wait=np.full(3, 2.5))
+    np.testing.assert_allclose(st.q, 2.5, rtol=1e-15)   # a constant signal is its own average
+
+
+def test_eq2_with_smoothed_status_by_hand():
+    from oracle import blackbox
+    st = blackbox.SmoothedStatus(q=np.array([1.0, 0.0]), p=np.array([0.01, 0.02]), d=np.array([0.1, 0.05]))
+    T = blackbox.eq2_latency(st, [100], [50], H=np.array([[20, 0]]))
+    # 1 + 0.01*80 + 0.1*50 = 6.8 ;  0 + 0.02*100 + 0.05*50 = 4.5
+    np.testing.assert_allclose(T, [[6.8, 4.5]], rtol=1e-14)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_numpy_selection_matches_brute_force(seed):
+    from oracle import blackbox
+    rng = np.random.default_rng(400 + seed)
+    n, M = 60, 7
+    T = rng.uniform(1, 10, (n, M))
+    T[:, 3] = T[:, 1]                              # exact ties in T
+    d = rng.uniform(0.1, 1.0, M)
+    d[5] = d[2]                                    # and in d
+    D = rng.uniform(0.5, 12, n)
+    ex = rng.integers(-1, M, n)
+    for exclude in (None, ex):
+        inst, slack, fb, Tc = blackbox.select(T, d, D, exclude)
+        for r in range(n):
+            pick, fall = brute.select(list(T[r]), list(d), D[r], -1 if exclude is None else int(ex[r]))
+            assert inst[r] == pick and bool(fb[r]) == fall
+            assert slack[r] == pytest.approx(D[r] - T[r, pick])
+    inst, _, _, _ = blackbox.select(T[:, :1], d[:1], D, np.zeros(n, dtype=np.int64))
+    assert np.all(inst == -1)                      # the only instance is barred
+
+
+def test_blend_end_points_and_midpoint(tiny):
+    from oracle import blackbox
+    fl, sim = tiny
+    M = fl.n_inst
+    rng = np.random.default_rng(5)
+    st = blackbox.SmoothedStatus(q=rng.uniform(0, 2, M), p=rng.uniform(1e-5, 1e-3, M), d=rng.uniform(0.01, 0.2, M))
+    c0, ln = fl.in_prompt, fl.in_len
+    hits = random_hits(rng, len(c0), M, c0)
+    D = fl.in_budget.astype(np.float64)
+    zero = blackbox.BlendedFleet(sim, fl, st, 0.0)
+    np.testing.assert_array_equal(zero.pair_T(c0, ln, hits=hits), sim.pair_T(c0, ln, hits=hits))
+    np.testing.assert_array_equal(zero.d, sim.d)
+    np.testing.assert_array_equal(zero.act_finish, sim.act_finish)
+    assert np.array_equal(zero.route(c0, ln, D, hits=hits).inst, sim.route(c0, ln, D, hits=hits).inst)
+    one = blackbox.BlendedFleet(sim, fl, st, 1.0)
+    H = blackbox.dense_hits(hits, len(c0), M, c0)
+    np.testing.assert_allclose(one.pair_T(c0, ln, hits=hits), blackbox.eq2_latency(st, c0, ln, H), rtol=1e-15)
+    assert np.array_equal(np.argsort(one.rank), np.lexsort((np.arange(M), -st.d)))
+    inst_a = np.repeat(np.arange(M), np.diff(fl.act_off))
+    np.testing.assert_allclose(one.act_finish, st.d[inst_a] * fl.act_rem, rtol=1e-15)
+    half = blackbox.BlendedFleet(sim, fl, st, 0.5)
+    np.testing.assert_allclose(half.pair_T(c0, ln), 0.5 * (sim.pair_T(c0, ln) + one.pair_T(c0, ln)), rtol=1e-14)
+    np.testing.assert_allclose(half.q_finish, 0.5 * (sim.q_finish + one.q_finish), rtol=1e-14)
