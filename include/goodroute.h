@@ -57,7 +57,7 @@ enum {
     GR_ERR_INVALID_ARG = -1, /* NULL where a pointer is required, negative size, bad class id */
     GR_ERR_TOO_LARGE = -2,   /* a size exceeds what the handle was created for, or a hard limit */
     GR_ERR_HIP = -3,         /* a HIP runtime call failed */
-    GR_ERR_NO_STATUS = -4,   /* gr_score_route before any gr_build_status / gr_risk_scan */
+    GR_ERR_NO_STATUS = -4,   /* gr_score_route before any gr_build_status / gr_risk_scan; a blend before gr_observe */
     GR_ERR_NOMEM = -5        /* host or device allocation failed in gr_create */
 };
 
@@ -191,6 +191,35 @@ int gr_risk_scan(gr_fleet* f,
                  uint8_t* out_flag, float* out_finish,
                  int32_t* out_target, float* out_target_slack, int32_t* out_n_flagged,
                  void* hip_stream);
+
+/*
+ * The paper's own status estimate (Sec. 3.3; Alg. 1 before it forms T(r,g)):
+ * q_g, p_g, d_g taken black-box from what was recently observed on the
+ * instance and smoothed by an exponential moving average,
+ *   x_g <- weight * sample_g + (1 - weight) * x_g,
+ * for each of the three terms that comes with a new sample (a term's first
+ * sample is its estimate).  Samples: the average waiting time of instance g,
+ * its prefill seconds per token, its decode seconds per token (TPOT).
+ *
+ *   weight       in [0, 1]
+ *   obs_wait, obs_prefill, obs_decode   DEVICE float[n_inst] each; NULL = no new sample of that term
+ * The estimates live in the handle, in double precision.
+ */
+int gr_observe(gr_fleet* f, double weight, const float* obs_wait, const float* obs_prefill,
+               const float* obs_decode, void* hip_stream);
+
+/*
+ * How much of that black-box estimate enters every figure the library
+ * produces.  With weight w every estimate is
+ *   (1 - w) * [white-box value] + w * [Eq. 2 with the smoothed q_g, p_g, d_g]:
+ * T(r,g) = q_g + p_g*(ctx0 - H) + d_g*pred_len for a pair; d_g itself for
+ * Alg. 1's argmax; d_g per remaining token for the finish time of a running
+ * request, q_g + p_g*prompt + d_g*length for a queued one.  w = 0 (the state
+ * after gr_create) is the white-box model alone, w = 1 the paper's estimator
+ * alone.  Takes effect at the next gr_build_status / gr_risk_scan.  Host call.
+ * GR_ERR_NO_STATUS if w > 0 before all three terms have been observed.
+ */
+int gr_set_blend(gr_fleet* f, double black_box_weight);
 
 /*
  * Synchronises the device and returns the OR of the GR_DEV_* bits raised by

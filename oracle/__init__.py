@@ -159,14 +159,18 @@ class RiskScan:
     target_slack: np.ndarray
 
 
-def risk_scan(fleet, act_rem_refreshed, act_budget, only: Optional[np.ndarray] = None) -> RiskScan:
+def risk_scan(fleet, act_rem_refreshed, act_budget, only: Optional[np.ndarray] = None,
+              view=None) -> RiskScan:
     """Sec. 3.4's periodic re-check against one snapshot of the fleet: simulate
     with the refreshed lengths; a request whose finish exceeds its budget is
     flagged and re-routed by Alg. 1 among the other instances, where it
     prefills prompt + generated tokens again and still has its refreshed
     length to decode.  ``only`` restricts target selection to a subset of
-    active-request indices (large fleets)."""
+    active-request indices (large fleets).  ``view`` maps the simulated fleet
+    to the object whose estimates are used (default: the simulation itself)."""
     sim = simulate(fleet, act_rem_refreshed)
+    if view is not None:        # e.g. the blend with the black-box status: same interface, other numbers
+        sim = view(sim)
     budget = np.asarray(act_budget, dtype=np.float64)
     flag = (sim.act_finish > budget).astype(np.uint8)
     n = len(flag)

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libgoodroute.so")
 
 EXPORTS = ("gr_create", "gr_destroy", "gr_build_status", "gr_score_route", "gr_score_route_cached",
-           "gr_risk_scan",
+           "gr_risk_scan", "gr_observe", "gr_set_blend",
            "gr_device_status", "gr_strerror", "gr_profile_enable", "gr_profile_read",
            "gr_profile_kernel_count", "gr_profile_kernel_name")
 
@@ -46,6 +46,10 @@ def lib() -> C.CDLL:
         l.gr_score_route_cached.argtypes = [p, i64, p, p, p, p, p, p, p, i64, p, p, p, p, p]
         l.gr_risk_scan.restype = C.c_int
         l.gr_risk_scan.argtypes = [p, p, p, p, p, i64, p, p, p, i64, p, p, p, p, p, p, p]
+        l.gr_observe.restype = C.c_int
+        l.gr_observe.argtypes = [p, C.c_double, p, p, p, p]
+        l.gr_set_blend.restype = C.c_int
+        l.gr_set_blend.argtypes = [p, C.c_double]
         l.gr_device_status.restype = C.c_int
         l.gr_device_status.argtypes = [p, C.POINTER(i32)]
         l.gr_profile_enable.restype = C.c_int
@@ -168,6 +172,16 @@ class Fleet:
             _dev(out_finish, f32, "out_finish", na), _dev(out_target, i32, "out_target", na),
             _dev(out_target_slack, f32, "out_target_slack", na),
             _dev(out_n_flagged, i32, "out_n_flagged", 1), _stream()), "gr_risk_scan")
+
+    def gr_observe(self, weight: float, obs_wait=None, obs_prefill=None, obs_decode=None) -> None:
+        import torch
+        f32, M = torch.float32, self.n_inst
+        _check(lib().gr_observe(self._h, float(weight), _dev(obs_wait, f32, "obs_wait", M),
+                                _dev(obs_prefill, f32, "obs_prefill", M),
+                                _dev(obs_decode, f32, "obs_decode", M), _stream()), "gr_observe")
+
+    def gr_set_blend(self, black_box_weight: float) -> None:
+        _check(lib().gr_set_blend(self._h, float(black_box_weight)), "gr_set_blend")
 
     def gr_profile_enable(self, max_launches: int) -> None:
         _check(lib().gr_profile_enable(self._h, int(max_launches)), "gr_profile_enable")

@@ -83,6 +83,7 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         dev_alloc(&f->cls, n_class) && dev_alloc(&f->inst_class, n_inst) &&
         dev_alloc(&f->tabR, tab) && dev_alloc(&f->tabGH, tab) && dev_alloc(&f->headGH, n_inst) &&
         dev_alloc(&f->hN, n_inst) && dev_alloc(&f->hD, n_inst) &&
+        dev_alloc(&f->emaQ, n_inst) && dev_alloc(&f->emaP, n_inst) && dev_alloc(&f->emaD, n_inst) &&
         dev_alloc(&f->rank_acc, n_inst) && dev_alloc(&f->rank, n_inst) && dev_alloc(&f->order, f->m_pad) && dev_alloc(&f->posK, f->m_pad) &&
         dev_alloc(&f->act_inst, f->max_active) && dev_alloc(&f->counters, 1) &&
         dev_alloc(&f->len_cnt, f->bins) && dev_alloc(&f->len_base, f->bins) &&
@@ -114,7 +115,7 @@ int gr_destroy(gr_fleet* f)
 {
     if (!f) return GR_OK;
     (void)hipDeviceSynchronize();
-    void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabGH, f->headGH, f->hN, f->hD, f->rank_acc,
+    void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabGH, f->headGH, f->hN, f->hD, f->emaQ, f->emaP, f->emaD, f->rank_acc,
                     f->rank, f->order, f->posK, f->act_inst, f->counters, f->len_cnt, f->len_base, f->row_len,
                     f->row_off, f->tile_off, f->len_row, f->totals, f->recs, f->memo};
     int rc = GR_OK;
@@ -212,6 +213,22 @@ int gr_risk_scan(gr_fleet* f, const int32_t* act_off, const int32_t* act_prompt,
     return launch_score(f, src, true, o, s);
 }
 
+int gr_observe(gr_fleet* f, double weight, const float* obs_wait, const float* obs_prefill,
+               const float* obs_decode, void* hip_stream)
+{
+    if (!f || !(weight >= 0.0 && weight <= 1.0)) return GR_ERR_INVALID_ARG;
+    if (!obs_wait && !obs_prefill && !obs_decode) return GR_OK;
+    return launch_ema(f, weight, obs_wait, obs_prefill, obs_decode, static_cast<hipStream_t>(hip_stream));
+}
+
+int gr_set_blend(gr_fleet* f, double black_box_weight)
+{
+    if (!f || !(black_box_weight >= 0.0 && black_box_weight <= 1.0)) return GR_ERR_INVALID_ARG;
+    if (black_box_weight > 0.0 && !(f->have_q && f->have_p && f->have_d)) return GR_ERR_NO_STATUS;
+    f->lam = black_box_weight;
+    return GR_OK;
+}
+
 int gr_device_status(gr_fleet* f, int32_t* out_bits)
 {
     if (!f || !out_bits) return GR_ERR_INVALID_ARG;
@@ -267,7 +284,7 @@ const char* gr_strerror(int code)
         case GR_ERR_INVALID_ARG: return "invalid argument";
         case GR_ERR_TOO_LARGE: return "size exceeds what the handle was created for or a hard limit";
         case GR_ERR_HIP: return "HIP runtime error";
-        case GR_ERR_NO_STATUS: return "no status built yet: call gr_build_status or gr_risk_scan first";
+        case GR_ERR_NO_STATUS: return "no status yet: gr_build_status / gr_risk_scan (or gr_observe) must come first";
         case GR_ERR_NOMEM: return "out of memory";
         default: return "unknown error";
     }

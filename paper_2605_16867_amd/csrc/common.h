@@ -100,6 +100,11 @@ struct gr_fleet {
     int64_t row_cap = 0;   // rows of the memo table
     int device = 0;
     bool has_status = false;
+    // smoothed black-box status (Sec. 3.3) and the weight it is blended in with
+    double lam = 0.0;        // as set; takes effect at the next status build
+    double lam_built = 0.0;  // the weight the current tables were built with
+    bool have_q = false, have_p = false, have_d = false;
+    double *emaQ = nullptr, *emaP = nullptr, *emaD = nullptr;   // [M] each
     // device memory: fleet description
     gr::ClassCoef* cls = nullptr;
     int* inst_class = nullptr;
@@ -161,6 +166,7 @@ struct StatusIn {
 
 // status.hip
 int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s);
+int launch_ema(gr_fleet* f, double w, const float* s_q, const float* s_p, const float* s_d, hipStream_t s);
 
 // score.hip
 size_t score_lds_bytes(const gr_fleet* f);

@@ -200,6 +200,7 @@ struct MemoArgs {
     const float2 *tabGH, *headGH;
     float* memo;
     int n_inst, m_pad, cap;
+    float keep;      // 1 - weight of the black-box estimate: scales the white-box curvature gamma
 };
 
 // E of every (distinct length, instance).  A workgroup of kMemoP waves takes
@@ -231,7 +232,7 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
     if (g >= 0) {
         N = a.hN[g];
         head = a.headGH[g];
-        gam = (float)a.cls[a.inst_class[g]].gamma;
+        gam = a.keep * (float)a.cls[a.inst_class[g]].gamma;
         GH = a.tabGH + (size_t)g * a.cap;
         const uint4* srcR = reinterpret_cast<const uint4*>(a.tabR + (size_t)g * a.cap);
         for (int c = lane; c * 8 < N; c += kWave) reinterpret_cast<uint4*>(sR)[c] = srcR[c];
@@ -847,7 +848,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         m.totals = f->totals; m.row_len = f->row_len; m.order = f->order; m.hN = f->hN;
         m.cls = f->cls; m.inst_class = f->inst_class;
         m.tabR = f->tabR; m.tabGH = f->tabGH; m.headGH = f->headGH; m.memo = f->memo;
-        m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.cap = f->cap;
+        m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.cap = f->cap; m.keep = (float)(1.0 - f->lam_built);
         // every workgroup walks all lengths; with few instances the lengths are dealt out to several
         const int gx = f->m_pad / kMemoP;
         const int64_t chunks = (max_rows + kMemoU - 1) / kMemoU;

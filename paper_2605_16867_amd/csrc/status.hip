@@ -36,6 +36,9 @@ struct BuildArgs {
     int* counters;
     int64_t n_active, n_queued;
     int n_inst, max_entries, max_len;
+    // blend with the smoothed black-box status (Sec. 3.3): weight lam on it, 0 = none
+    double lam;
+    const double *emaQ, *emaP, *emaD;
 };
 
 // Median of three; the compiler turns this shape into one v_med3_u32.
@@ -198,6 +201,11 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     long long Ytot, Xtot, Ctot;
     long long Y = wave_excl_scan(yl, Ytot), X = wave_excl_scan(xl, Xtot), Pc = wave_excl_scan(cl, Ctot);
 
+    // with a blend, every estimate below is keep * (white-box value) + lam * (Eq. 2 with the smoothed status)
+    const bool blended = a.lam != 0.0;
+    const double keep = 1.0 - a.lam;
+    const double bq = blended ? a.emaQ[g] : 0.0, bp = blended ? a.emaP[g] : 0.0, bd = blended ? a.emaD[g] : 0.0;
+
     // table entry v describes the segment after the v+1 shortest requests, n of them still running:
     //   E_g(L) = Gq + L * H + tri(L) * gamma * (n + 1)
     //   Gq = q + beta * Y + gamma * X,   H = alpha + beta * (n + 1) + gamma * S
@@ -214,13 +222,17 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
         const double n_after = (double)(N - v - 1), S_next = (double)(Ctot - Pc);
         const double Yd = (double)Y, Xd = (double)X, Rd = (double)Rr;
         tR[r] = valid ? (uint16_t)R[r] : (uint16_t)0xFFFFu;
-        tGH[r] = make_float2((float)(q + (cc.beta * Yd + cc.gamma * Xd)),
-                             (float)(cc.alpha + (cc.beta * (n_after + 1.0) + cc.gamma * S_next)));
+        double Gq = q + (cc.beta * Yd + cc.gamma * Xd);
+        double Hs = cc.alpha + (cc.beta * (n_after + 1.0) + cc.gamma * S_next);
+        if (blended) { Gq = keep * Gq + a.lam * bq; Hs = keep * Hs + a.lam * bd; }
+        tGH[r] = make_float2((float)Gq, (float)Hs);
         if (valid) {
             // every product below is an integer below 2^53: exact
             const double I1 = Yd + n_after * Rd;
             const double I2 = Xd + Rd * S_next + n_after * (double)triR;
-            const double fin = q + fma(cc.gamma, I2, fma(cc.beta, I1, cc.alpha * Rd));
+            double fin = q + fma(cc.gamma, I2, fma(cc.beta, I1, cc.alpha * Rd));
+            if (blended)   // black-box finish: d per remaining token; a queued request also waits and prefills
+                fin = keep * fin + a.lam * (idx[r] < A ? bd * Rd : (bq + bp * (double)cx[r]) + bd * Rd);
             if (idx[r] < A) {
                 a.out_act_finish[a0 + idx[r]] = (float)fin;
                 if (a.act_budget) a.out_flag[a0 + idx[r]] = fin > (double)a.act_budget[a0 + idx[r]];
@@ -254,10 +266,13 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     }
     if (lane == 0) {
         const double Cd = (double)Ctot;
-        a.headGH[g] = make_float2((float)q, (float)(cc.alpha + (cc.beta * (double)(N + 1) + cc.gamma * Cd)));
+        double Gq0 = q, H0 = cc.alpha + (cc.beta * (double)(N + 1) + cc.gamma * Cd);
+        if (blended) { Gq0 = keep * Gq0 + a.lam * bq; H0 = keep * H0 + a.lam * bd; }
+        a.headGH[g] = make_float2((float)Gq0, (float)H0);
         a.hN[g] = N;
         a.rank_acc[g] = 0;
-        const double d = fma(cc.gamma, Cd, fma(cc.beta, (double)N, cc.alpha));
+        double d = fma(cc.gamma, Cd, fma(cc.beta, (double)N, cc.alpha));
+        if (blended) d = keep * d + a.lam * bd;
         a.hD[g] = d;
         if (a.out_d) a.out_d[g] = d;
     }
@@ -290,6 +305,7 @@ __global__ __launch_bounds__(kBlock) void k_rank_count(const double* __restrict_
 __global__ __launch_bounds__(kBlock) void k_rank_final(const int* __restrict__ rank_acc, int n_inst, int m_pad,
                                                        const ClassCoef* __restrict__ cls,
                                                        const int* __restrict__ inst_class,
+                                                       double lam, const double* __restrict__ emaP,
                                                        int* __restrict__ rank, int* __restrict__ order,
                                                        float2* __restrict__ posK, int* __restrict__ out_rank)
 {
@@ -299,12 +315,29 @@ __global__ __launch_bounds__(kBlock) void k_rank_final(const int* __restrict__ r
         const ClassCoef cc = cls[inst_class[g]];
         rank[g] = r;
         order[r] = g;
-        posK[r] = make_float2((float)cc.delta, (float)cc.gamma);
+        // T = E + c0 * (delta + gamma * L); blended: keep * that + lam * p_g * c0
+        const double keep = 1.0 - lam;
+        posK[r] = lam != 0.0 ? make_float2((float)(keep * cc.delta + lam * emaP[g]), (float)(keep * cc.gamma))
+                             : make_float2((float)cc.delta, (float)cc.gamma);
         if (out_rank) out_rank[g] = r;
     } else if (g < m_pad) {
         order[g] = -1;     // positions past the last instance
         posK[g] = make_float2(0.f, 0.f);
     }
+}
+
+// One step of the exponential moving average of Alg. 1, q <- w * sample + (1 - w) * q, for
+// each of the three status terms that has a new sample; a term's first sample is its estimate.
+__global__ __launch_bounds__(kBlock) void k_ema(int n_inst, double w, const float* __restrict__ s_q,
+                                                const float* __restrict__ s_p, const float* __restrict__ s_d,
+                                                int first_q, int first_p, int first_d,
+                                                double* __restrict__ q, double* __restrict__ p, double* __restrict__ d)
+{
+    const int g = blockIdx.x * kBlock + threadIdx.x;
+    if (g >= n_inst) return;
+    if (s_q) q[g] = first_q ? (double)s_q[g] : w * (double)s_q[g] + (1.0 - w) * q[g];
+    if (s_p) p[g] = first_p ? (double)s_p[g] : w * (double)s_p[g] + (1.0 - w) * p[g];
+    if (s_d) d[g] = first_d ? (double)s_d[g] : w * (double)s_d[g] + (1.0 - w) * d[g];
 }
 
 template <int kEPL>
@@ -315,6 +348,15 @@ void launch_build(const BuildArgs& b, int M, hipStream_t s)
 }
 
 }  // namespace
+
+int launch_ema(gr_fleet* f, double w, const float* s_q, const float* s_p, const float* s_d, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_ema, dim3((f->n_inst + kBlock - 1) / kBlock), dim3(kBlock), 0, s, f->n_inst, w, s_q, s_p, s_d,
+                       !f->have_q, !f->have_p, !f->have_d, f->emaQ, f->emaP, f->emaD);
+    if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
+    f->have_q |= s_q != nullptr; f->have_p |= s_p != nullptr; f->have_d |= s_d != nullptr;
+    return GR_OK;
+}
 
 int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
 {
@@ -330,6 +372,7 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
     b.rank_acc = f->rank_acc; b.counters = f->counters;
     b.n_active = in.n_active; b.n_queued = in.n_queued;
     b.n_inst = f->n_inst; b.max_entries = f->max_entries; b.max_len = f->max_len;
+    b.lam = f->lam; b.emaQ = f->emaQ; b.emaP = f->emaP; b.emaD = f->emaD;
     const int M = f->n_inst;
     {
         ProfScope ps(f, kBuild, s);
@@ -350,11 +393,12 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
     {
         ProfScope ps(f, kRankFinal, s);
         hipLaunchKernelGGL(k_rank_final, dim3((f->m_pad + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
-                           f->rank_acc, M, f->m_pad, f->cls, f->inst_class, f->rank, f->order, f->posK,
-                           in.out_rank);
+                           f->rank_acc, M, f->m_pad, f->cls, f->inst_class, f->lam, f->emaP, f->rank, f->order,
+                           f->posK, in.out_rank);
     }
     if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
     f->has_status = true;
+    f->lam_built = f->lam;
     return GR_OK;
 }
 

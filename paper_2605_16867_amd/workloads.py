@@ -226,3 +226,24 @@ def cached_prefixes(fl: Fleet, mean_hits: float = 2.0, seed: int = 0):
     frac = rng.uniform(0.0, 1.0, n)
     ln = np.maximum(1, np.ceil(frac * fl.in_prompt[owner])).astype(np.int32)
     return off, inst, ln
+
+
+def observed_status(fl: Fleet, rounds: int = 3, seed: int = 0):
+    """Black-box observations of every instance, as Sec. 3.3 collects them: per
+    round the average waiting time (seconds), the prefill seconds per token and
+    the decode seconds per token (TPOT) of each instance, float32.  Values are
+    the instance class's nominal figures at its current load times lognormal
+    jitter (sigma 0.3), waiting times uniform in [0, 2] s.  Returns a list of
+    (ema_weight, wait, prefill, decode) with weight 0.3; draw order per round:
+    wait, prefill, decode."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    M = fl.n_inst
+    n_g = (np.diff(fl.act_off) + np.diff(fl.q_off)).astype(np.float64)
+    c = fl.inst_class
+    out = []
+    for _ in range(rounds):
+        wait = rng.uniform(0.0, 2.0, M).astype(np.float32)
+        prefill = (fl.coef["delta"][c] * rng.lognormal(0.0, 0.3, M)).astype(np.float32)
+        decode = ((fl.coef["alpha"][c] + fl.coef["beta"][c] * n_g) * rng.lognormal(0.0, 0.3, M)).astype(np.float32)
+        out.append((0.3, wait, prefill, decode))
+    return out

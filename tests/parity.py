@@ -128,11 +128,13 @@ def make_handle(fl, max_requests: Optional[int] = None, max_entries: Optional[in
 
 
 def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit: int = 1 << 25,
-                  exclude=None, hits=None):
+                  exclude=None, hits=None, blackbox=None):
     """Run the whole path on the GPU and check it.  ``sample``: number of
     requests (and of active requests) checked against the reference; None = all.
     ``hits``: (hit_off, hit_inst, hit_len) cached prefixes of the incoming requests
-    (routes through gr_score_route_cached)."""
+    (routes through gr_score_route_cached).  ``blackbox``: (rounds, weight) with
+    rounds = [(ema_weight, wait, prefill, decode), ..] float32 arrays or None per term:
+    fed to gr_observe, then blended in with gr_set_blend(weight)."""
     import torch
     dev = "cuda:0"
     rep = {}
@@ -141,6 +143,16 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
     na, nq, R = len(fl.act_prompt), len(fl.q_prompt), len(fl.in_prompt)
     h = make_handle(fl)
     rng = np.random.default_rng(seed)
+    view = lambda s, rem=None: s
+    if blackbox is not None:
+        rounds, lam = blackbox
+        status = oracle.SmoothedStatus()
+        f32t = lambda x: None if x is None else torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(dev)
+        for w, ow, op, od in rounds:
+            h.gr_observe(w, f32t(ow), f32t(op), f32t(od))
+            status.observe(w, *[None if x is None else np.asarray(x, dtype=np.float32) for x in (ow, op, od)])
+        h.gr_set_blend(lam)
+        view = lambda s, rem=None: oracle.BlendedFleet(s, fl, status, lam, act_rem=rem)
 
     # ---- step 1: status
     fin = torch.full((na,), float("nan"), dtype=torch.float32, device=dev)
@@ -150,7 +162,7 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
     h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"],
                       d["q_off"], d["q_prompt"], d["q_len"], fin, qfin, dd, rk)
     torch.cuda.synchronize()
-    sim = oracle.simulate(fl)
+    sim = view(oracle.simulate(fl))
     e = rel_err(fin.cpu().numpy(), sim.act_finish)
     assert na == 0 or e.max() <= EPS, f"active finish rel err {e.max():.3g}"
     rep["finish_rel_err"] = float(e.max()) if na else 0.0
@@ -207,7 +219,8 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
                        flag, fin2, tgt, tsl, nfl)
         torch.cuda.synchronize()
         idx = np.arange(na) if sample is None or sample >= na else np.sort(rng.choice(na, sample, replace=False))
-        rs = oracle.risk_scan(fl, fl.act_rem_refreshed, fl.act_budget, only=idx)
+        rs = oracle.risk_scan(fl, fl.act_rem_refreshed, fl.act_budget, only=idx,
+                              view=lambda s: view(s, fl.act_rem_refreshed))
         e = rel_err(fin2.cpu().numpy(), rs.finish)
         assert e.max() <= EPS, f"risk-scan finish rel err {e.max():.3g}"
         budget = fl.act_budget.astype(np.float64)

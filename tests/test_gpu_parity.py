@@ -111,3 +111,48 @@ def test_heavy_fleet_with_cached_prefixes_sampled():
     hits = workloads.cached_prefixes(fl, mean_hits=2.0, seed=4)
     rep = parity.run_and_check(fl, sample=2048, hits=hits)
     report("heavy + prefixes", rep)
+
+
+# --------------------------------------------------------------------------- EMA-smoothed black-box status (Sec. 3.3)
+@pytest.mark.parametrize("lam", [0.25, 1.0])
+def test_mid_fleet_blended_with_black_box_status(lam):
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=2.0, occupancy_jitter=True, seed=31))
+    rounds = workloads.observed_status(fl, rounds=3, seed=1)
+    # the terms are not always observed together
+    rounds.append((0.5, rounds[0][1], None, None))
+    rep = parity.run_and_check(fl, blackbox=(rounds, lam))
+    report(f"mid blend {lam}", rep)
+
+
+def test_blend_with_prefixes_and_exclusions():
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=1.5, seed=32))
+    hits = workloads.cached_prefixes(fl, mean_hits=3.0, seed=6)
+    ex = np.random.default_rng(2).integers(-1, fl.n_inst, len(fl.in_prompt)).astype(np.int32)
+    rep = parity.run_and_check(fl, exclude=ex, hits=hits, blackbox=(workloads.observed_status(fl, 2, seed=2), 0.6))
+    report("mid blend 0.6 + prefixes + exclude", rep)
+
+
+def test_heavy_fleet_blended_sampled():
+    fl = workloads.make_fleet(workloads.spec("heavy"))
+    rep = parity.run_and_check(fl, sample=1024, blackbox=(workloads.observed_status(fl, 2, seed=3), 0.5))
+    report("heavy blend 0.5", rep)
+
+
+def test_blend_zero_is_the_white_box_model_and_errors():
+    from paper_2605_16867_amd import binding
+    fl = workloads.make_fleet(workloads.spec("tiny"))
+    rep0 = parity.run_and_check(fl)
+    rep1 = parity.run_and_check(fl, blackbox=(workloads.observed_status(fl, 1, seed=4), 0.0))
+    assert rep0 == rep1
+    h = parity.make_handle(fl)
+    with pytest.raises(binding.GoodRouteError) as e:
+        h.gr_set_blend(0.5)                       # nothing observed yet
+    assert e.value.code == -4
+    with pytest.raises(binding.GoodRouteError) as e:
+        h.gr_set_blend(1.5)
+    assert e.value.code == -1
+    with pytest.raises(binding.GoodRouteError) as e:
+        h.gr_observe(-0.1)
+    assert e.value.code == -1
+    h.gr_set_blend(0.0)
+    h.close()
