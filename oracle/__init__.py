@@ -188,4 +188,56 @@ def risk_scan(fleet, act_rem_refreshed, act_budget, only: Optional[np.ndarray] =
     return RiskScan(sim, sim.act_finish, flag, target, tslack)
 
 
+class _Extended:
+    """A fleet with more queued requests appended per instance (plain arrays, as workloads.Fleet)."""
+
+    def __init__(self, fleet, extra):
+        M = len(fleet.inst_class)
+        self.coef, self.inst_class = fleet.coef, fleet.inst_class
+        self.act_off, self.act_prompt = fleet.act_off, fleet.act_prompt
+        self.act_gen, self.act_rem = fleet.act_gen, fleet.act_rem
+        qp, ql, off = [], [], [0]
+        for g in range(M):
+            a, b = int(fleet.q_off[g]), int(fleet.q_off[g + 1])
+            qp += list(fleet.q_prompt[a:b]) + [e[0] for e in extra[g]]
+            ql += list(fleet.q_len[a:b]) + [e[1] for e in extra[g]]
+            off.append(len(qp))
+        self.q_off = np.array(off, dtype=np.int32)
+        self.q_prompt = np.array(qp, dtype=np.int32)
+        self.q_len = np.array(ql, dtype=np.int32)
+
+
+def route_with_feedback(fleet, c0, length, deadline, chunk: int, exclude=None, follow=None):
+    """Alg. 1 with the fleet's status kept up to date between decisions, the way
+    the paper's proxy routes (one request after the other, each seeing the
+    requests routed before it): the batch is taken ``chunk`` requests at a time
+    in arrival order; a chunk is decided against one snapshot, then each of its
+    requests joins the queue of the instance it was sent to (prompt = its
+    tokens to prefill, length = its predicted decode length), and the next
+    chunk sees the fleet simulated anew.  ``chunk = 1`` is request by request.
+
+    ``follow``: instance per request to commit instead of this function's own
+    choice (to check another implementation step by step from the states it
+    really went through).  Returns (Routing, list of per-chunk (rows, T, rank)
+    with T the [chunk, M] latencies and rank the capability order the chunk saw)."""
+    c0, length = _i32(c0), _i32(length)
+    deadline = _f64(deadline)
+    n, M = len(c0), len(fleet.inst_class)
+    extra = [[] for _ in range(M)]
+    out = Routing(np.zeros(n, np.int32), np.zeros(n, np.float64), np.zeros(n, np.uint8), np.zeros(n, np.float64))
+    seen = []
+    for s in range(0, n, chunk):
+        rows = np.arange(s, min(s + chunk, n))
+        sim = simulate(_Extended(fleet, extra))
+        ex = None if exclude is None else _i32(exclude)[rows]
+        r = sim.route(c0[rows], length[rows], deadline[rows], exclude=ex)
+        out.inst[rows], out.slack[rows], out.fallback[rows], out.T[rows] = r.inst, r.slack, r.fallback, r.T
+        seen.append((rows, sim.pair_T(c0[rows], length[rows]), sim.rank))
+        commit = r.inst if follow is None else np.asarray(follow)[rows]
+        for i, g in zip(rows, commit):
+            if g >= 0:
+                extra[int(g)].append((int(c0[i]), int(length[i])))
+    return out, seen
+
+
 from .blackbox import BlendedFleet, SmoothedStatus  # noqa: E402,F401

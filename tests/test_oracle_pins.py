@@ -520,3 +520,56 @@ def test_blend_end_points_and_midpoint(tiny):
     half = blackbox.BlendedFleet(sim, fl, st, 0.5)
     np.testing.assert_allclose(half.pair_T(c0, ln), 0.5 * (sim.pair_T(c0, ln) + one.pair_T(c0, ln)), rtol=1e-14)
     np.testing.assert_allclose(half.q_finish, 0.5 * (sim.q_finish + one.q_finish), rtol=1e-14)
+
+
+# --------------------------------------------------------------------------- routing with status feedback (Alg. 1, request after request)
+@pytest.mark.parametrize("seed", range(4))
+def test_feedback_routing_matches_brute_force_sequence(seed):
+    """chunk = 1 against a pure-Python proxy: every request is scored by replaying each instance
+    with it appended, Alg. 1 picks, and the request is really appended to the instance it got."""
+    rng = np.random.default_rng(500 + seed)
+    coefs, inst_class, actives, queued = random_tiny(rng, n_inst=4)
+    f = make(coefs, inst_class, actives, queued)
+    n = 25
+    c0 = rng.integers(1, 60, n)
+    ln = rng.integers(1, 31, n)
+    solo = np.array([brute.latency_if_routed(coefs[0], [], [], int(c0[r]), int(ln[r])) for r in range(n)])
+    D = solo * rng.uniform(1.0, 12.0, n)
+    ex = rng.integers(-1, 4, n).astype(np.int32)
+    got, _ = oracle.route_with_feedback(f, c0, ln, D, chunk=1, exclude=ex)
+    queues = [list(q) for q in queued]
+    for r in range(n):
+        T = [brute.latency_if_routed(coefs[inst_class[g]], actives[g], queues[g], int(c0[r]), int(ln[r]))
+             for g in range(4)]
+        d = [brute.replay(coefs[inst_class[g]], actives[g], queues[g])[1] for g in range(4)]
+        pick, fb = brute.select(T, d, D[r], int(ex[r]))
+        assert got.inst[r] == pick and bool(got.fallback[r]) == fb
+        assert got.slack[r] == pytest.approx(D[r] - T[pick], rel=1e-9, abs=1e-12)
+        queues[pick].append((int(c0[r]), int(ln[r])))
+    snap = oracle.simulate(f).route(c0, ln, D, exclude=ex)
+    assert not np.allclose(snap.slack, got.slack)  # later requests do see the earlier ones
+
+
+def test_feedback_routing_limits(tiny):
+    fl, sim = tiny
+    D = fl.in_budget.astype(np.float64) * 3
+    n = len(fl.in_prompt)
+    # one chunk holding the whole batch is the snapshot decision
+    whole, seen = oracle.route_with_feedback(fl, fl.in_prompt, fl.in_len, D, chunk=n)
+    snap = sim.route(fl.in_prompt, fl.in_len, D)
+    assert np.array_equal(whole.inst, snap.inst) and np.array_equal(whole.slack, snap.slack) and len(seen) == 1
+    # what one routed request adds to its instance: its prefill to q_g, beta + gamma*prompt to d_g
+    one, seen = oracle.route_with_feedback(fl, fl.in_prompt[:2], fl.in_len[:2], D[:2], chunk=1)
+    g = int(one.inst[0])
+    c = int(fl.inst_class[g])
+    extended = oracle.simulate(oracle._Extended(fl, [[(int(fl.in_prompt[0]), int(fl.in_len[0]))] if i == g else []
+                                                     for i in range(fl.n_inst)]))
+    assert extended.q[g] == pytest.approx(sim.q[g] + fl.coef["delta"][c] * fl.in_prompt[0], rel=1e-12)
+    assert extended.d[g] == pytest.approx(sim.d[g] + fl.coef["beta"][c] + fl.coef["gamma"][c] * fl.in_prompt[0], rel=1e-12)
+    others = np.arange(fl.n_inst) != g
+    assert np.array_equal(extended.q[others], sim.q[others]) and np.array_equal(extended.d[others], sim.d[others])
+    np.testing.assert_array_equal(seen[1][1], extended.pair_T(fl.in_prompt[1:2], fl.in_len[1:2]))
+    # following someone else's commits: the second request sees the state those commits made
+    forced = np.array([(g + 1) % fl.n_inst, 0], dtype=np.int32)
+    _, seen_f = oracle.route_with_feedback(fl, fl.in_prompt[:2], fl.in_len[:2], D[:2], chunk=1, follow=forced)
+    assert not np.array_equal(seen_f[1][1], seen[1][1])
