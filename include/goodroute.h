@@ -166,6 +166,34 @@ int gr_score_route_cached(gr_fleet* f, int64_t n_req,
                           float* out_T, void* hip_stream);
 
 /*
+ * Step 2 with the status kept up to date between decisions.  The paper's proxy
+ * runs Alg. 1 request after request, refreshing the instances' status before
+ * each decision, so that a request sees the ones routed before it; a batch
+ * scored against one snapshot sends every similar request to the same
+ * instance.  Here the batch is taken `chunk` requests at a time, in order: a
+ * chunk is decided as by gr_score_route, then each of its requests joins the
+ * queue of the instance it was sent to (prompt = ctx0, length = pred_len; it is
+ * prefilled behind the queue and decodes with the batch), the status is
+ * rebuilt, and the next chunk is decided.  chunk = 1 is the paper's order;
+ * chunk >= n_req is gr_score_route.  On return the handle's tables hold the
+ * status with all n_req requests in place; the next gr_build_status or
+ * gr_risk_scan starts from the caller's arrays again.
+ *
+ * The arrays passed to the last gr_build_status / gr_risk_scan are read again
+ * and must still be valid and unchanged.  An instance takes routed requests
+ * while it holds fewer than max_entries_per_inst entries; beyond that the
+ * request is still reported but no longer counted (GR_DEV_ENTRIES_DROPPED).
+ * Cost: one status rebuild and one scoring pass per chunk.
+ *
+ *   chunk      requests per decision round, >= 1 (cut to max_requests)
+ * Other arguments as gr_score_route (no out_T).
+ */
+int gr_route_feedback(gr_fleet* f, int64_t n_req, int64_t chunk,
+                      const int32_t* ctx0, const int32_t* pred_len, const float* budget,
+                      const int32_t* exclude_inst,
+                      int32_t* out_inst, float* out_slack, uint8_t* out_fallback, void* hip_stream);
+
+/*
  * Step 3 (Sec. 3.4, periodic re-check).  Rebuilds the status from refreshed
  * remaining lengths (as gr_build_status, replacing the handle's tables), flags
  * every active request whose expected finish exceeds its budget

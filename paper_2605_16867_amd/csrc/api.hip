@@ -86,6 +86,8 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         dev_alloc(&f->emaQ, n_inst) && dev_alloc(&f->emaP, n_inst) && dev_alloc(&f->emaD, n_inst) &&
         dev_alloc(&f->rank_acc, n_inst) && dev_alloc(&f->rank, n_inst) && dev_alloc(&f->order, f->m_pad) && dev_alloc(&f->posK, f->m_pad) &&
         dev_alloc(&f->act_inst, f->max_active) && dev_alloc(&f->counters, 1) &&
+        dev_alloc(&f->pend_cnt, n_inst) && dev_alloc(&f->pend_prompt, tab) && dev_alloc(&f->pend_len, tab) &&
+        dev_alloc(&f->scratch_finish, f->max_active) &&
         dev_alloc(&f->len_cnt, f->bins) && dev_alloc(&f->len_base, f->bins) &&
         dev_alloc(&f->row_len, f->row_cap) && dev_alloc(&f->row_off, f->row_cap + 1) &&
         dev_alloc(&f->tile_off, f->row_cap + 1) && dev_alloc(&f->len_row, f->bins) && dev_alloc(&f->totals, 4) &&
@@ -100,8 +102,9 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
     const hipError_t e3 = hipMemset(f->counters, 0, sizeof(int));
     const hipError_t e4 = hipMemset(f->len_cnt, 0, sizeof(int) * f->bins);
     const hipError_t e5 = hipMemset(f->totals, 0, sizeof(int) * 4);
+    const hipError_t e6 = hipMemset(f->pend_cnt, 0, sizeof(int) * n_inst);
     free(host);
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess ||
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess || e6 != hipSuccess ||
         hipDeviceSynchronize() != hipSuccess) {
         gr_destroy(f);
         return GR_ERR_HIP;
@@ -116,7 +119,8 @@ int gr_destroy(gr_fleet* f)
     if (!f) return GR_OK;
     (void)hipDeviceSynchronize();
     void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabGH, f->headGH, f->hN, f->hD, f->emaQ, f->emaP, f->emaD, f->rank_acc,
-                    f->rank, f->order, f->posK, f->act_inst, f->counters, f->len_cnt, f->len_base, f->row_len,
+                    f->rank, f->order, f->posK, f->act_inst, f->pend_cnt, f->pend_prompt, f->pend_len,
+                    f->scratch_finish, f->counters, f->len_cnt, f->len_base, f->row_len,
                     f->row_off, f->tile_off, f->len_row, f->totals, f->recs, f->memo};
     int rc = GR_OK;
     for (void* p : ptrs)
@@ -180,6 +184,38 @@ int gr_score_route_cached(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const
     ScoreOut o{};
     o.inst = out_inst; o.slack = out_slack; o.fallback = out_fallback; o.T = out_T;
     return launch_hits(f, src, hit_off, hit_inst, hit_len, n_hits, o, static_cast<hipStream_t>(hip_stream));
+}
+
+int gr_route_feedback(gr_fleet* f, int64_t n_req, int64_t chunk, const int32_t* ctx0,
+                      const int32_t* pred_len, const float* budget, const int32_t* exclude_inst,
+                      int32_t* out_inst, float* out_slack, uint8_t* out_fallback, void* hip_stream)
+{
+    if (!f || n_req < 0 || chunk < 1) return GR_ERR_INVALID_ARG;
+    if (!f->has_status) return GR_ERR_NO_STATUS;
+    if (n_req == 0) return GR_OK;
+    if (!ctx0 || !pred_len || !budget || !out_inst || !out_slack) return GR_ERR_INVALID_ARG;
+    if (chunk > f->max_requests) chunk = f->max_requests;
+    if (chunk < 1) return GR_ERR_TOO_LARGE;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // rebuilds start from the caller's last status inputs; what they report goes to scratch
+    StatusIn in = f->last_in;
+    in.use_pending = 1;
+    in.act_budget = nullptr; in.out_flag = nullptr;
+    in.out_act_finish = f->scratch_finish; in.out_q_finish = nullptr; in.out_d = nullptr; in.out_rank = nullptr;
+    for (int64_t s0 = 0; s0 < n_req; s0 += chunk) {
+        const int64_t n = n_req - s0 < chunk ? n_req - s0 : chunk;
+        ReqSrc src{};
+        src.ctx0 = ctx0 + s0; src.pred_len = pred_len + s0; src.budget = budget + s0;
+        src.exclude = exclude_inst ? exclude_inst + s0 : nullptr;
+        src.n = n;
+        ScoreOut o{};
+        o.inst = out_inst + s0; o.slack = out_slack + s0; o.fallback = out_fallback ? out_fallback + s0 : nullptr;
+        int rc = launch_score(f, src, false, o, s);
+        if (rc == GR_OK) rc = launch_commit(f, n, out_inst + s0, ctx0 + s0, pred_len + s0, s);
+        if (rc == GR_OK) rc = launch_status(f, in, s);
+        if (rc != GR_OK) return rc;
+    }
+    return GR_OK;
 }
 
 int gr_risk_scan(gr_fleet* f, const int32_t* act_off, const int32_t* act_prompt,

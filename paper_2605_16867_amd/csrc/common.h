@@ -85,6 +85,18 @@ struct Profiler {
     std::vector<int> ids;            // kernel id of each recorded pair
 };
 
+struct StatusIn {
+    const int *act_off, *act_prompt, *act_gen, *act_rem;
+    const int *q_off, *q_prompt, *q_len;
+    const float* act_budget;  // null unless flags are wanted
+    int64_t n_active, n_queued;
+    float *out_act_finish, *out_q_finish;
+    double* out_d;
+    int* out_rank;
+    uint8_t* out_flag;
+    int use_pending = 0;      // count the requests routed since the caller's status (feedback routing)
+};
+
 }  // namespace gr
 
 struct gr_fleet {
@@ -120,6 +132,12 @@ struct gr_fleet {
     int* order = nullptr;    // [m_pad] order[rank[g]] = g
     float2* posK = nullptr;  // [m_pad] (delta, gamma) of the instance at each position of the capability order
     int* act_inst = nullptr; // [max_active] instance of each active request
+    // feedback routing: the caller's last status inputs, and the requests routed since, per instance
+    gr::StatusIn last_in{};
+    int* pend_cnt = nullptr;      // [M]
+    int* pend_prompt = nullptr;   // [M][cap]
+    int* pend_len = nullptr;      // [M][cap]
+    float* scratch_finish = nullptr;  // [max_active] finish times of rebuilds nobody asked to see
     int* counters = nullptr; // [1] GR_DEV_* bits
     // scoring workspace
     int* len_cnt = nullptr;   // [bins] requests per length; all zero between calls
@@ -153,19 +171,10 @@ struct ProfScope {
     }
 };
 
-struct StatusIn {
-    const int *act_off, *act_prompt, *act_gen, *act_rem;
-    const int *q_off, *q_prompt, *q_len;
-    const float* act_budget;  // null unless flags are wanted
-    int64_t n_active, n_queued;
-    float *out_act_finish, *out_q_finish;
-    double* out_d;
-    int* out_rank;
-    uint8_t* out_flag;
-};
 
 // status.hip
 int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s);
+int launch_commit(gr_fleet* f, int64_t n, const int* inst, const int* ctx0, const int* pred_len, hipStream_t s);
 int launch_ema(gr_fleet* f, double w, const float* s_q, const float* s_p, const float* s_d, hipStream_t s);
 
 // score.hip

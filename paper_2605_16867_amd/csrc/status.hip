@@ -36,6 +36,10 @@ struct BuildArgs {
     int* counters;
     int64_t n_active, n_queued;
     int n_inst, max_entries, max_len;
+    // requests routed since the caller's status (feedback routing): per instance, queued behind the queue
+    int* pend_cnt;
+    const int *pend_prompt, *pend_len;
+    int use_pending;     // 0: a fresh status from the caller, the lists are emptied
     // blend with the smoothed black-box status (Sec. 3.3): weight lam on it, 0 = none
     double lam;
     const double *emaQ, *emaP, *emaD;
@@ -148,7 +152,11 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     int status = 0;
     if (A > a.max_entries) { A = a.max_entries; status |= GR_DEV_ENTRIES_DROPPED; }
     if (Q > a.max_entries - A) { Q = a.max_entries - A; status |= GR_DEV_ENTRIES_DROPPED; }
-    const int N = A + Q;
+    int P = a.use_pending ? min(a.pend_cnt[g], kCap) : 0;
+    if (P > a.max_entries - A - Q) { P = a.max_entries - A - Q; status |= GR_DEV_ENTRIES_DROPPED; }
+    const int N = A + Q + P;
+    const int* pp = a.pend_prompt + (size_t)g * kCap;
+    const int* pl = a.pend_len + (size_t)g * kCap;
 
     // load, entry i = 64 r + lane: one sort word per entry = (remaining length << kIdxBits) | i
     uint32_t key[kEPL];
@@ -163,9 +171,13 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
                 rem = a.act_rem[a0 + i];
                 c = a.act_prompt[a0 + i] + a.act_gen[a0 + i];
                 a.act_inst[a0 + i] = g;
-            } else {
+            } else if (i < A + Q) {
                 rem = a.q_len[q0 + i - A];
                 c = a.q_prompt[q0 + i - A];
+                qsum += c;
+            } else {
+                rem = pl[i - A - Q];
+                c = pp[i - A - Q];
                 qsum += c;
             }
             if (rem < 0 || rem > a.max_len) { rem = min(max(rem, 0), a.max_len); status |= GR_DEV_LEN_CLAMPED; }
@@ -175,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
         key[r] = word;
     }
     if (status) atomicOr(&a.counters[0], status);
-    if (Q > 0) qsum = wave_sum(qsum);       // Q is the same in every lane
+    if (Q + P > 0) qsum = wave_sum(qsum);   // Q and P are the same in every lane
     const double q = cc.delta * (double)qsum;
 
     bitonic_sort<kEPL>(key, lane);
@@ -236,7 +248,7 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
             if (idx[r] < A) {
                 a.out_act_finish[a0 + idx[r]] = (float)fin;
                 if (a.act_budget) a.out_flag[a0 + idx[r]] = fin > (double)a.act_budget[a0 + idx[r]];
-            } else if (a.out_q_finish) {
+            } else if (a.out_q_finish && idx[r] < A + Q) {
                 a.out_q_finish[q0 + idx[r] - A] = (float)fin;
             }
         }
@@ -271,6 +283,7 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
         a.headGH[g] = make_float2((float)Gq0, (float)H0);
         a.hN[g] = N;
         a.rank_acc[g] = 0;
+        if (!a.use_pending) a.pend_cnt[g] = 0;
         double d = fma(cc.gamma, Cd, fma(cc.beta, (double)N, cc.alpha));
         if (blended) d = keep * d + a.lam * bd;
         a.hD[g] = d;
@@ -340,6 +353,43 @@ __global__ __launch_bounds__(kBlock) void k_ema(int n_inst, double w, const floa
     if (s_d) d[g] = first_d ? (double)s_d[g] : w * (double)s_d[g] + (1.0 - w) * d[g];
 }
 
+// Requests that were routed join the queue of their instance (feedback routing): one slot of
+// the instance's list per request.  Many requests of a chunk go to the same instance and
+// atomics on one address are served one after the other, so the lanes of a wave that chose
+// the same instance reserve their slots with one atomic.
+__global__ __launch_bounds__(kBlock) void k_commit(int64_t n, const int* __restrict__ inst,
+                                                   const int* __restrict__ ctx0, const int* __restrict__ pred_len,
+                                                   int* __restrict__ pend_cnt, int* __restrict__ pend_prompt,
+                                                   int* __restrict__ pend_len, int cap, int n_inst,
+                                                   int* __restrict__ counters)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int lane = lane_id();
+    int g = i < n ? inst[i] : -1;
+    if (g >= n_inst) g = -1;
+    const bool act = g >= 0;
+    unsigned long long todo = __ballot(act);
+    int slot = 0;
+    while (todo) {
+        const int leader = __ffsll((long long)todo) - 1;
+        const int gl = __builtin_amdgcn_readlane(g, leader);
+        const unsigned long long same = __ballot(act && g == gl);
+        int base = 0;
+        if (lane == leader) base = atomicAdd(&pend_cnt[gl], __popcll(same));
+        base = __builtin_amdgcn_readlane(base, leader);
+        if (act && g == gl) slot = base + __popcll(same & ((1ull << lane) - 1ull));
+        todo &= ~same;
+    }
+    if (act) {
+        if (slot < cap) {
+            pend_prompt[(size_t)g * cap + slot] = ctx0[i];
+            pend_len[(size_t)g * cap + slot] = pred_len[i];
+        } else {
+            atomicOr(&counters[0], GR_DEV_ENTRIES_DROPPED);
+        }
+    }
+}
+
 template <int kEPL>
 void launch_build(const BuildArgs& b, int M, hipStream_t s)
 {
@@ -348,6 +398,14 @@ void launch_build(const BuildArgs& b, int M, hipStream_t s)
 }
 
 }  // namespace
+
+int launch_commit(gr_fleet* f, int64_t n, const int* inst, const int* ctx0, const int* pred_len, hipStream_t s)
+{
+    if (n == 0) return GR_OK;
+    hipLaunchKernelGGL(k_commit, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, n, inst, ctx0, pred_len,
+                       f->pend_cnt, f->pend_prompt, f->pend_len, f->cap, f->n_inst, f->counters);
+    return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
+}
 
 int launch_ema(gr_fleet* f, double w, const float* s_q, const float* s_p, const float* s_d, hipStream_t s)
 {
@@ -372,6 +430,8 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
     b.rank_acc = f->rank_acc; b.counters = f->counters;
     b.n_active = in.n_active; b.n_queued = in.n_queued;
     b.n_inst = f->n_inst; b.max_entries = f->max_entries; b.max_len = f->max_len;
+    b.pend_cnt = f->pend_cnt; b.pend_prompt = f->pend_prompt; b.pend_len = f->pend_len;
+    b.use_pending = in.use_pending;
     b.lam = f->lam; b.emaQ = f->emaQ; b.emaP = f->emaP; b.emaD = f->emaD;
     const int M = f->n_inst;
     {
@@ -399,6 +459,7 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
     if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
     f->has_status = true;
     f->lam_built = f->lam;
+    if (!in.use_pending) f->last_in = in;     // what a later feedback routing rebuilds from
     return GR_OK;
 }
 

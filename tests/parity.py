@@ -246,3 +246,60 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
     assert h.gr_device_status() == 0, "device status bits raised on in-contract input"
     h.close()
     return rep
+
+
+def run_feedback_and_check(fl, chunk: int, n_req: Optional[int] = None, exclude=None):
+    """gr_route_feedback against the reference, round by round: the reference follows the
+    instances the GPU committed, so every round is compared on the state the GPU really had."""
+    import torch
+    dev = "cuda:0"
+    rep = {}
+    d = upload(fl, dev)
+    M = len(fl.inst_class)
+    R = len(fl.in_prompt) if n_req is None else n_req
+    c0, ln, D32 = fl.in_prompt[:R], fl.in_len[:R], fl.in_budget[:R]
+    me = int(max(np.diff(fl.act_off) + np.diff(fl.q_off)))
+    h = make_handle(fl, max_requests=max(R, 1), max_entries=min(me + R, 2048))
+    na = len(fl.act_prompt)
+    fin = torch.zeros(na, dtype=torch.float32, device=dev)
+    h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"],
+                      d["q_off"], d["q_prompt"], d["q_len"], fin)
+    fin0 = fin.clone()
+    inst = torch.full((R,), -7, dtype=torch.int32, device=dev)
+    slack = torch.zeros(R, dtype=torch.float32, device=dev)
+    fb = torch.zeros(R, dtype=torch.uint8, device=dev)
+    ex_np = None if exclude is None else np.ascontiguousarray(exclude[:R], dtype=np.int32)
+    h.gr_route_feedback(chunk, d["in_prompt"][:R], d["in_len"][:R], d["in_budget"][:R], inst, slack,
+                        exclude_inst=None if ex_np is None else torch.from_numpy(ex_np).to(dev), out_fallback=fb)
+    torch.cuda.synchronize()
+    assert torch.equal(fin, fin0), "the caller's finish times were overwritten by a rebuild"
+    G, S, F = inst.cpu().numpy().astype(np.int64), slack.cpu().numpy(), fb.cpu().numpy()
+    D = D32.astype(np.float64)
+    ref, seen = oracle.route_with_feedback(fl, c0, ln, D, chunk, exclude=ex_np, follow=G)
+    amb = 0
+    for k, (rows, T, rank) in enumerate(seen):
+        rr = {}
+        check_choices(f"round{k}", T, D[rows], rank, None if ex_np is None else ex_np[rows], G[rows], S[rows], rr,
+                      fallback=F[rows])
+        amb += rr[f"round{k}_ambiguous"]
+    rep["rounds"], rep["ambiguous"], rep["n"] = len(seen), amb, R
+    rep["instances_used"] = int(len(np.unique(G)))
+    if amb == 0:        # nothing hinged on the band: the reference on its own takes the same path
+        free, _ = oracle.route_with_feedback(fl, c0, ln, D, chunk, exclude=ex_np)
+        assert np.array_equal(free.inst, G)
+    # the handle now holds the status with every request in place: a probe batch sees it
+    extra = [[] for _ in range(M)]
+    for i, g in enumerate(G):
+        if g >= 0:
+            extra[int(g)].append((int(c0[i]), int(ln[i])))
+    final = oracle.simulate(oracle._Extended(fl, extra))
+    P = min(256, len(fl.in_prompt))
+    pi = torch.full((P,), -7, dtype=torch.int32, device=dev)
+    ps = torch.zeros(P, dtype=torch.float32, device=dev)
+    h.gr_score_route(d["in_prompt"][:P], d["in_len"][:P], d["in_budget"][:P], pi, ps)
+    torch.cuda.synchronize()
+    check_choices("probe", final.pair_T(fl.in_prompt[:P], fl.in_len[:P]), fl.in_budget[:P].astype(np.float64),
+                  final.rank, None, pi.cpu().numpy().astype(np.int64), ps.cpu().numpy(), rep)
+    assert h.gr_device_status() == 0, "device status bits raised on in-contract input"
+    h.close()
+    return rep

@@ -156,3 +156,28 @@ def test_blend_zero_is_the_white_box_model_and_errors():
     assert e.value.code == -1
     h.gr_set_blend(0.0)
     h.close()
+
+
+# --------------------------------------------------------------------------- routing with status feedback
+@pytest.mark.parametrize("chunk", [1, 16, 100, 512])
+def test_feedback_routing_mid_fleet(chunk):
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=3.0, occupancy_jitter=True, seed=41))
+    rep = parity.run_feedback_and_check(fl, chunk, n_req=512)
+    report(f"feedback chunk {chunk}", rep)
+    assert rep["rounds"] == -(-512 // chunk)
+
+
+def test_feedback_routing_spreads_the_herd():
+    """Tight deadlines: one snapshot sends the whole batch to a few instances; feedback uses more."""
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=1.0, seed=42))
+    snap = parity.run_feedback_and_check(fl, 512, n_req=512)
+    fed = parity.run_feedback_and_check(fl, 8, n_req=512)
+    report("feedback herd", {"snapshot_instances": snap["instances_used"], "feedback_instances": fed["instances_used"]})
+    assert fed["instances_used"] >= snap["instances_used"]
+
+
+def test_feedback_routing_large_fleet_with_exclusions():
+    fl = workloads.make_fleet(workloads.spec("large", slo_scale=4.0, seed=43))
+    ex = np.random.default_rng(4).integers(-1, fl.n_inst, 1024).astype(np.int32)
+    rep = parity.run_feedback_and_check(fl, 128, n_req=1024, exclude=ex)
+    report("feedback large", rep)
