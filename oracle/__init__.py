@@ -39,7 +39,7 @@ def _load():
         lib = C.CDLL(build())
         p = C.c_void_p
         lib.gro_simulate.restype = p
-        lib.gro_simulate.argtypes = [C.c_int32, C.c_int32] + [p] * 14
+        lib.gro_simulate.argtypes = [C.c_int32, C.c_int32] + [p] * 15
         lib.gro_free.argtypes = [p]
         lib.gro_status.argtypes = [p, p, p, p]
         lib.gro_step_table.argtypes = [p, C.c_int32, p]
@@ -78,7 +78,7 @@ class SimulatedFleet:
     """Result of simulating every instance of a fleet step by step."""
 
     def __init__(self, coef, inst_class, act_off, act_prompt, act_gen, act_rem,
-                 q_off, q_prompt, q_len):
+                 q_off, q_prompt, q_len, cap=None):
         lib = _load()
         self.n_inst = int(len(inst_class))
         self._keep = [_f64(coef[k]) for k in ("delta", "alpha", "beta", "gamma")]
@@ -86,9 +86,10 @@ class SimulatedFleet:
                 _i32(q_off), _i32(q_prompt), _i32(q_len)]
         self.act_finish = np.zeros(len(args[2]), dtype=np.float64)
         self.q_finish = np.zeros(len(args[6]), dtype=np.float64)
+        self._cap = None if cap is None else _i32(cap)      # concurrent requests per instance (Sec. 3.1)
         self._h = lib.gro_simulate(self.n_inst, len(self._keep[0]),
                                    *[_ptr(a) for a in self._keep], *[_ptr(a) for a in args],
-                                   _ptr(self.act_finish), _ptr(self.q_finish))
+                                   _ptr(self._cap), _ptr(self.act_finish), _ptr(self.q_finish))
         if not self._h:
             raise MemoryError("gro_simulate failed")
         self.q = np.zeros(self.n_inst, dtype=np.float64)
@@ -144,10 +145,11 @@ class SimulatedFleet:
 
 
 def simulate(fleet, act_rem=None) -> SimulatedFleet:
-    """fleet: any object with the array attributes of workloads.Fleet."""
+    """fleet: any object with the array attributes of workloads.Fleet; an
+    optional attribute ``batch_cap`` (int per instance) bounds each batch."""
     return SimulatedFleet(fleet.coef, fleet.inst_class, fleet.act_off, fleet.act_prompt,
                           fleet.act_gen, fleet.act_rem if act_rem is None else act_rem,
-                          fleet.q_off, fleet.q_prompt, fleet.q_len)
+                          fleet.q_off, fleet.q_prompt, fleet.q_len, cap=getattr(fleet, "batch_cap", None))
 
 
 @dataclass
@@ -194,6 +196,8 @@ class _Extended:
     def __init__(self, fleet, extra):
         M = len(fleet.inst_class)
         self.coef, self.inst_class = fleet.coef, fleet.inst_class
+        if getattr(fleet, "batch_cap", None) is not None:
+            self.batch_cap = fleet.batch_cap
         self.act_off, self.act_prompt = fleet.act_off, fleet.act_prompt
         self.act_gen, self.act_rem = fleet.act_gen, fleet.act_rem
         qp, ql, off = [], [], [0]

@@ -69,14 +69,24 @@ static double *dup_d(const double *src, size_t n)
 /*
  * Simulate one instance (Sec. 3.3's "batched serving mode", made explicit).
  *
- * Queued requests are prefilled back to back first (prefill has priority and
- * stalls decoding, there is no batch-size cap); then every request of the
- * instance decodes together.  One step emits one token for every batch member:
+ * At most `cap` requests decode together (Sec. 3.1: the number of requests an
+ * instance serves concurrently is bounded by its memory).  Queued requests are
+ * admitted in queue order whenever the batch has room, at time 0 and after
+ * every decode step: an admission prefills the request (prefill has priority
+ * and stalls decoding) and puts it into the batch.  With room for everybody
+ * (cap larger than the number of requests) all queued requests are prefilled
+ * back to back at time 0.  Requests that are already running keep running even
+ * if they outnumber the cap.  One step emits one token for every batch member:
  * its remaining length drops by one and its context grows by one; a request
  * whose remaining length reaches zero finishes at the end of that step.
  * Times are measured from now = 0.
+ *
+ * A request that arrives now is last in the queue: q_out is the time at which
+ * it would be admitted (the queue ahead of it is in, and the batch has room),
+ * and w_out[s] the time of the s decode steps after that moment (nobody else
+ * joins any more).  d_out is the duration of the next decode step that runs.
  */
-static int simulate_instance(double delta, double alpha, double beta, double gamma,
+static int simulate_instance(double delta, double alpha, double beta, double gamma, int32_t cap,
                              int32_t n_act, const int32_t *a_prompt, const int32_t *a_gen,
                              const int32_t *a_rem,
                              int32_t n_q, const int32_t *q_prompt, const int32_t *q_len,
@@ -90,57 +100,65 @@ static int simulate_instance(double delta, double alpha, double beta, double gam
     if (!rem || !ctx || !who) { free(rem); free(ctx); free(who); return -1; }
 
     double t = 0.0;
-    int32_t smax = 0;
-    for (int32_t j = 0; j < n_q; ++j) {          /* queued: prefill, then join the batch */
-        t += delta * (double)q_prompt[j];
-        rem[n_act + j] = q_len[j];
-        ctx[n_act + j] = q_prompt[j];
-        who[n_act + j] = n_act + j;
-    }
-    double q = t;
+    int32_t nb = n_act, next_q = 0;
     for (int32_t i = 0; i < n_act; ++i) {        /* actives are already in the batch */
         rem[i] = a_rem[i];
         ctx[i] = (int64_t)a_prompt[i] + a_gen[i];
         who[i] = i;
     }
-    for (int32_t j = 0; j < n; ++j) if (rem[j] > smax) smax = rem[j];
 
-    double *w = (double *)malloc((size_t)(smax + 1) * sizeof(double));
-    if (!w) { free(rem); free(ctx); free(who); return -1; }
-    w[0] = 0.0;
+    double *w = NULL;
+    double t_admit = 0.0;      /* when a request arriving now would be admitted */
+    int32_t s_admit = -1;      /* decode steps done by then; -1: not reached yet */
+    int32_t s = 0, smax = 0;
+    int have_d = 0;
+    double elapsed = 0.0;      /* decode time since t_admit */
+    *d_out = alpha;            /* an idle instance would take alpha */
 
-    /* the instance's decode step time right now; an idle instance would take alpha */
-    {
-        int64_t c = 0;
-        for (int32_t j = 0; j < n; ++j) c += ctx[j];
-        *d_out = fma(gamma, (double)c, fma(beta, (double)n, alpha));
-    }
-
-    int32_t nb = n, s = 0;
-    double elapsed = 0.0;                        /* decode time since q */
-    while (nb > 0) {
+    for (;;) {
+        while (next_q < n_q && nb < cap) {       /* admit the head of the queue */
+            t += delta * (double)q_prompt[next_q];
+            rem[nb] = q_len[next_q];
+            ctx[nb] = q_prompt[next_q];
+            who[nb] = n_act + next_q;
+            ++nb; ++next_q;
+        }
+        if (s_admit < 0 && next_q == n_q && nb < cap) {
+            t_admit = t;
+            s_admit = s;
+            for (int32_t j = 0; j < nb; ++j) if (rem[j] > smax) smax = rem[j];
+            w = (double *)malloc((size_t)(smax + 1) * sizeof(double));
+            if (!w) { free(rem); free(ctx); free(who); return -1; }
+            w[0] = 0.0;
+        }
+        if (nb == 0) break;
         int64_t c = 0;
         for (int32_t j = 0; j < nb; ++j) c += ctx[j];
         double step = fma(gamma, (double)c, fma(beta, (double)nb, alpha));
-        elapsed += step;
+        if (!have_d) { *d_out = step; have_d = 1; }
         ++s;
-        w[s] = elapsed;
+        if (s_admit >= 0) {                      /* no admissions any more: decode time adds up on its own */
+            elapsed += step;
+            w[s - s_admit] = elapsed;
+            t = t_admit + elapsed;
+        } else {
+            t += step;
+        }
         int32_t m = 0;
         for (int32_t j = 0; j < nb; ++j) {
             rem[j] -= 1;
             ctx[j] += 1;
             if (rem[j] <= 0) {
-                double fin = q + elapsed;
-                if (who[j] < n_act) { if (a_finish) a_finish[who[j]] = fin; }
-                else if (q_finish) q_finish[who[j] - n_act] = fin;
+                if (who[j] < n_act) { if (a_finish) a_finish[who[j]] = t; }
+                else if (q_finish) q_finish[who[j] - n_act] = t;
             } else {
                 rem[m] = rem[j]; ctx[m] = ctx[j]; who[m] = who[j]; ++m;
             }
         }
         nb = m;
     }
-    *q_out = q;
-    *smax_out = s;
+    *q_out = t_admit;
+    *smax_out = smax;
     *w_out = w;
     free(rem); free(ctx); free(who);
     return 0;
@@ -150,7 +168,8 @@ static int simulate_instance(double delta, double alpha, double beta, double gam
  * Simulate every instance; returns a handle holding q_g, d_g and the step
  * table of each instance, and writes each request's expected finish time.
  * a_finish / q_finish may be NULL.  All arrays are host arrays; act_off and
- * q_off are CSR offsets of length n_inst + 1.
+ * q_off are CSR offsets of length n_inst + 1; cap[g] bounds the batch of
+ * instance g (NULL: unbounded).
  */
 gro_fleet *gro_simulate(int32_t n_inst, int32_t n_class,
                         const double *delta, const double *alpha,
@@ -159,6 +178,7 @@ gro_fleet *gro_simulate(int32_t n_inst, int32_t n_class,
                         const int32_t *act_off, const int32_t *act_prompt,
                         const int32_t *act_gen, const int32_t *act_rem,
                         const int32_t *q_off, const int32_t *q_prompt, const int32_t *q_len,
+                        const int32_t *cap /* per instance, may be NULL: no bound */,
                         double *a_finish, double *q_finish)
 {
     gro_fleet *f = (gro_fleet *)calloc(1, sizeof(gro_fleet));
@@ -180,7 +200,7 @@ gro_fleet *gro_simulate(int32_t n_inst, int32_t n_class,
     for (int32_t g = 0; g < n_inst; ++g) {
         int c = inst_class[g];
         int32_t a0 = act_off[g], q0 = q_off[g];
-        int rc = simulate_instance(delta[c], alpha[c], beta[c], gamma[c],
+        int rc = simulate_instance(delta[c], alpha[c], beta[c], gamma[c], cap ? cap[g] : INT32_MAX,
                                    act_off[g + 1] - a0, act_prompt + a0, act_gen + a0, act_rem + a0,
                                    q_off[g + 1] - q0, q_prompt + q0, q_len + q0,
                                    a_finish ? a_finish + a0 : NULL, q_finish ? q_finish + q0 : NULL,

@@ -573,3 +573,78 @@ def test_feedback_routing_limits(tiny):
     forced = np.array([(g + 1) % fl.n_inst, 0], dtype=np.int32)
     _, seen_f = oracle.route_with_feedback(fl, fl.in_prompt[:2], fl.in_len[:2], D[:2], chunk=1, follow=forced)
     assert not np.array_equal(seen_f[1][1], seen[1][1])
+
+
+# --------------------------------------------------------------------------- batch cap (Sec. 3.1's memory bound on concurrency)
+@pytest.mark.parametrize("seed", range(8))
+def test_batch_cap_matches_brute_force_replay(seed):
+    rng = np.random.default_rng(600 + seed)
+    coefs, inst_class, actives, queued = random_tiny(rng, n_inst=4, max_n=8)
+    # more queued requests than the default helper makes, so that the queue really waits
+    queued = [[(int(rng.integers(1, 50)), int(rng.integers(1, 21))) for _ in range(int(rng.integers(0, 7)))]
+              for _ in range(4)]
+    f = make(coefs, inst_class, actives, queued)
+    f.batch_cap = np.array([int(rng.integers(1, len(actives[g]) + len(queued[g]) + 3)) for g in range(4)], np.int32)
+    sim = oracle.simulate(f)
+    reqs = [(int(rng.integers(1, 60)), int(rng.integers(1, 31)), int(rng.integers(0, 2))) for _ in range(10)]
+    hits = (np.arange(11, dtype=np.int32) * 4, np.tile(np.arange(4, dtype=np.int32), 10),
+            np.repeat(np.array([r[2] * (r[0] // 2) for r in reqs], dtype=np.int32), 4))
+    T = sim.pair_T([r[0] for r in reqs], [r[1] for r in reqs], hits=hits)
+    waited = False
+    for g in range(4):
+        co, cap = coefs[inst_class[g]], int(f.batch_cap[g])
+        fin, admitted, first = brute.replay_capped(co, actives[g], queued[g], cap)
+        got = np.concatenate([sim.act_finish[f.act_off[g]:f.act_off[g + 1]],
+                              sim.q_finish[f.q_off[g]:f.q_off[g + 1]]])
+        np.testing.assert_allclose(got, np.array(fin, dtype=np.float64), rtol=1e-12)
+        assert sim.d[g] == pytest.approx(co[1] if first is None else first, rel=1e-12)
+        waited |= any(a > 0 for a in admitted)
+        for r, (c0, ln, hit) in enumerate(reqs):
+            want, when = brute.latency_if_routed_capped(co, actives[g], queued[g], cap, c0, ln, hit * (c0 // 2))
+            assert T[r, g] == pytest.approx(want, rel=1e-11)
+            assert sim.q[g] == pytest.approx(when, rel=1e-12, abs=1e-15)
+    assert waited or seed > 3
+
+
+def test_batch_cap_one_is_a_single_server_queue():
+    """cap = 1: requests run alone, one after the other; every finish time is a sum of solo latencies."""
+    co = (0.01, 1.0, 0.1, 0.001)
+    solo = lambda ctx, L: L * (co[1] + co[2]) + co[3] * (ctx * L + L * (L - 1) / 2)
+    f = make([co], [0], [[(10, 2, 3)]], [[(5, 4), (7, 2), (3, 6)]])
+    f.batch_cap = np.array([1], np.int32)
+    sim = oracle.simulate(f)
+    t = solo(12, 3)
+    assert sim.act_finish[0] == pytest.approx(t, rel=1e-13)
+    for j, (P, L) in enumerate([(5, 4), (7, 2), (3, 6)]):
+        t += co[0] * P + solo(P, L)
+        assert sim.q_finish[j] == pytest.approx(t, rel=1e-13)
+    assert sim.q[0] == pytest.approx(t, rel=1e-13)          # a newcomer is admitted when the last one is done
+    assert sim.d[0] == pytest.approx(co[1] + co[2] + co[3] * 12, rel=1e-13)
+    T = sim.pair_T([8], [5])
+    assert T[0, 0] == pytest.approx(t + co[0] * 8 + solo(8, 5), rel=1e-13)
+
+
+def test_batch_cap_limits(tiny):
+    fl, sim = tiny
+    from copy import copy
+    n_g = np.diff(fl.act_off) + np.diff(fl.q_off)
+    roomy = copy(fl)
+    roomy.batch_cap = (n_g + 1).astype(np.int32)           # room for everybody and a newcomer: no cap at all
+    s2 = oracle.simulate(roomy)
+    assert np.array_equal(s2.act_finish, sim.act_finish) and np.array_equal(s2.q, sim.q) and np.array_equal(s2.d, sim.d)
+    assert np.array_equal(s2.pair_T(fl.in_prompt, fl.in_len), sim.pair_T(fl.in_prompt, fl.in_len))
+    # a tighter cap never lets a newcomer in earlier
+    prev = sim.q
+    for shrink in (0, 4, 16, 40):
+        capped = copy(fl)
+        capped.batch_cap = np.maximum(1, n_g - shrink).astype(np.int32)
+        q = oracle.simulate(capped).q
+        assert np.all(q >= prev - 1e-12)
+        prev = q
+    # exactly full: the newcomer waits for the first departure
+    full = copy(fl)
+    full.batch_cap = n_g.astype(np.int32)
+    sf = oracle.simulate(full)
+    first_departure = np.array([min(np.concatenate([sf.act_finish[fl.act_off[g]:fl.act_off[g + 1]],
+                                                    sf.q_finish[fl.q_off[g]:fl.q_off[g + 1]]])) for g in range(fl.n_inst)])
+    np.testing.assert_allclose(sf.q, first_departure, rtol=1e-13)
