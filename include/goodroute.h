@@ -250,6 +250,29 @@ int gr_observe(gr_fleet* f, double weight, const float* obs_wait, const float* o
 int gr_set_blend(gr_fleet* f, double black_box_weight);
 
 /*
+ * The paper's second constraint (Sec. 3.1): the number of requests an instance
+ * serves concurrently is bounded by its memory.  With a cap B_g, at most B_g
+ * requests of instance g decode together: queued requests are admitted in
+ * queue order whenever the batch has room (at time 0 and after every decode
+ * step); an admission prefills the request, stalling the batch, and puts it
+ * into the batch.  Requests already running keep running even if they
+ * outnumber the cap.  A request that arrives now is last in the queue, so
+ *   q_g = the time at which it would be admitted,
+ * after which nobody else joins and T(r,g) = q_g + delta*(ctx0 - H) + [its
+ * pred_len decode steps in the batch as it is then].  d_g is the duration of
+ * the next decode step that runs.  Every call uses the caps from the next
+ * gr_build_status / gr_risk_scan on.  With room for everybody and a newcomer
+ * (B_g > entries of g) nothing changes.
+ *
+ *   cap   HOST int32[n_inst], each >= 1; NULL removes the caps.
+ * Host call; waits for the device.
+ *
+ * With gr_route_feedback, requests committed in the same chunk queue up in an
+ * unspecified order (chunk = 1 is in request order).
+ */
+int gr_set_batch_cap(gr_fleet* f, const int32_t* cap);
+
+/*
  * Synchronises the device and returns the OR of the GR_DEV_* bits raised by
  * kernels since gr_create (HOST int32 out).  Not for the hot path.
  */

@@ -87,7 +87,7 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         dev_alloc(&f->rank_acc, n_inst) && dev_alloc(&f->rank, n_inst) && dev_alloc(&f->order, f->m_pad) && dev_alloc(&f->posK, f->m_pad) &&
         dev_alloc(&f->act_inst, f->max_active) && dev_alloc(&f->counters, 1) &&
         dev_alloc(&f->pend_cnt, n_inst) && dev_alloc(&f->pend_prompt, tab) && dev_alloc(&f->pend_len, tab) &&
-        dev_alloc(&f->scratch_finish, f->max_active) &&
+        dev_alloc(&f->scratch_finish, f->max_active) && dev_alloc(&f->batch_cap, n_inst) &&
         dev_alloc(&f->len_cnt, f->bins) && dev_alloc(&f->len_base, f->bins) &&
         dev_alloc(&f->row_len, f->row_cap) && dev_alloc(&f->row_off, f->row_cap + 1) &&
         dev_alloc(&f->tile_off, f->row_cap + 1) && dev_alloc(&f->len_row, f->bins) && dev_alloc(&f->totals, 4) &&
@@ -120,7 +120,7 @@ int gr_destroy(gr_fleet* f)
     (void)hipDeviceSynchronize();
     void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabGH, f->headGH, f->hN, f->hD, f->emaQ, f->emaP, f->emaD, f->rank_acc,
                     f->rank, f->order, f->posK, f->act_inst, f->pend_cnt, f->pend_prompt, f->pend_len,
-                    f->scratch_finish, f->counters, f->len_cnt, f->len_base, f->row_len,
+                    f->scratch_finish, f->batch_cap, f->counters, f->len_cnt, f->len_base, f->row_len,
                     f->row_off, f->tile_off, f->len_row, f->totals, f->recs, f->memo};
     int rc = GR_OK;
     for (void* p : ptrs)
@@ -262,6 +262,18 @@ int gr_set_blend(gr_fleet* f, double black_box_weight)
     if (!f || !(black_box_weight >= 0.0 && black_box_weight <= 1.0)) return GR_ERR_INVALID_ARG;
     if (black_box_weight > 0.0 && !(f->have_q && f->have_p && f->have_d)) return GR_ERR_NO_STATUS;
     f->lam = black_box_weight;
+    return GR_OK;
+}
+
+int gr_set_batch_cap(gr_fleet* f, const int32_t* cap)
+{
+    if (!f) return GR_ERR_INVALID_ARG;
+    if (!cap) { f->has_cap = false; return GR_OK; }
+    for (int g = 0; g < f->n_inst; ++g)
+        if (cap[g] < 1) return GR_ERR_INVALID_ARG;
+    if (hipDeviceSynchronize() != hipSuccess) return GR_ERR_HIP;
+    if (hipMemcpy(f->batch_cap, cap, sizeof(int) * f->n_inst, hipMemcpyHostToDevice) != hipSuccess) return GR_ERR_HIP;
+    f->has_cap = true;
     return GR_OK;
 }
 

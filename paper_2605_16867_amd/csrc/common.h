@@ -138,6 +138,8 @@ struct gr_fleet {
     int* pend_prompt = nullptr;   // [M][cap]
     int* pend_len = nullptr;      // [M][cap]
     float* scratch_finish = nullptr;  // [max_active] finish times of rebuilds nobody asked to see
+    int* batch_cap = nullptr;     // [M] requests that may decode together on each instance
+    bool has_cap = false;
     int* counters = nullptr; // [1] GR_DEV_* bits
     // scoring workspace
     int* len_cnt = nullptr;   // [bins] requests per length; all zero between calls

@@ -40,6 +40,7 @@ struct BuildArgs {
     int* pend_cnt;
     const int *pend_prompt, *pend_len;
     int use_pending;     // 0: a fresh status from the caller, the lists are emptied
+    const int* batch_cap;   // per instance: requests that may decode together; null = no bound
     // blend with the smoothed black-box status (Sec. 3.3): weight lam on it, 0 = none
     double lam;
     const double *emaQ, *emaP, *emaD;
@@ -131,7 +132,7 @@ constexpr int kBuildWaves = kBlock / kWave;
 
 constexpr int log2_of(int v) { return v <= 1 ? 0 : 1 + log2_of(v / 2); }
 
-template <int kEPL>
+template <int kEPL, bool kCapAware>
 __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
 {
     extern __shared__ uint32_t smem[];
@@ -141,7 +142,9 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int g = blockIdx.x * kBuildWaves + wave;
     if (g >= a.n_inst) return;
-    int* ctx = reinterpret_cast<int*>(smem) + wave * kCap;     // this wave's contexts, by entry index
+    int* ctx = reinterpret_cast<int*>(smem) + wave * 3 * kCap;  // this wave's contexts, by entry index
+    int* olen = ctx + kCap;    // under a batch cap: length and context as given (ctx then holds them
+    int* octx = olen + kCap;   // as they are when a newcomer would be admitted)
 
     const ClassCoef cc = a.cls[a.inst_class[g]];
     // offsets are clamped into the arrays, so broken CSR data cannot index outside them
@@ -188,7 +191,108 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     }
     if (status) atomicOr(&a.counters[0], status);
     if (Q + P > 0) qsum = wave_sum(qsum);   // Q and P are the same in every lane
-    const double q = cc.delta * (double)qsum;
+    double q = cc.delta * (double)qsum;
+
+    // with a blend, every estimate below is keep * (white-box value) + lam * (Eq. 2 with the smoothed status)
+    const bool blended = a.lam != 0.0;
+    const double keep = 1.0 - a.lam;
+    const double bq = blended ? a.emaQ[g] : 0.0, bp = blended ? a.emaP[g] : 0.0, bd = blended ? a.emaD[g] : 0.0;
+    // what a request of the instance is told: entry i, white-box finish time, its length and context as given
+    auto report = [&](int i, double fin, double len0, double ctx0) {
+        if (blended)   // black-box finish: d per remaining token; a queued request also waits and prefills
+            fin = keep * fin + a.lam * (i < A ? bd * len0 : (bq + bp * ctx0) + bd * len0);
+        if (i < A) {
+            a.out_act_finish[a0 + i] = (float)fin;
+            if (a.act_budget) a.out_flag[a0 + i] = fin > (double)a.act_budget[a0 + i];
+        } else if (a.out_q_finish && i < A + Q) {
+            a.out_q_finish[q0 + i - A] = (float)fin;
+        }
+    };
+
+    // ---- batch cap (Sec. 3.1: concurrency bounded by memory).  With room for everybody and a
+    // newcomer nothing changes.  Otherwise the instance is played forward, event by event (the
+    // queue's head is admitted whenever the batch has room; between two departures the batch is
+    // fixed and its time is a closed form), up to the moment a newcomer would be admitted: q_g is
+    // that moment, and the requests still running then, with what is left of them, are what the
+    // closed form below is built on.  Requests that leave earlier get their finish time here.
+    // (kCapAware is a kernel of its own: the event loop's registers would cost the plain build a wave per SIMD)
+    const int cap_g = kCapAware ? max(a.batch_cap[g], 1) : 0x7fffffff;
+    const bool capped = kCapAware && cap_g <= N;
+    int Nrun = N;
+    double d_first = -1.0;
+    if (capped) {
+        int fstep[kEPL], cbase[kEPL];     // decode step at which the entry leaves; its context minus the step count
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r) {
+            const int i = r * kWave + lane;
+            const int len0 = i < N ? (int)(key[r] >> kIdxBits) : 0, c0 = i < N ? ctx[i] : 0;
+            fstep[r] = i < A ? len0 : (i < N ? 0x7fffffff : 0);     // queued: not in yet; none: gone
+            cbase[r] = c0;
+            if (i < N) { olen[i] = len0; octx[i] = c0; }
+        }
+        long long C = 0;
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r) C += r * kWave + lane < A ? cbase[r] : 0;
+        C = wave_sum(C);
+        int n = A, s = 0, next_q = A;     // batch size, steps done, next entry of the queue
+        double t = 0.0;
+        for (int guard = 0; guard <= 2 * N + 2; ++guard) {
+            const int k = min(cap_g - n, N - next_q);
+            if (k > 0) {                   // admit entries next_q .. next_q + k - 1: prefill, then into the batch
+                long long sumP = 0;
+#pragma unroll
+                for (int r = 0; r < kEPL; ++r) {
+                    const int i = r * kWave + lane;
+                    if (i >= next_q && i < next_q + k) {
+                        fstep[r] = s + (int)(key[r] >> kIdxBits);
+                        sumP += cbase[r];
+                        cbase[r] -= s;
+                    }
+                }
+                sumP = wave_sum(sumP);
+                t += cc.delta * (double)sumP;
+                n += k; C += sumP; next_q += k;
+            }
+            if (next_q == N && n < cap_g) break;      // a newcomer would be admitted now
+            // next departure
+            int smin = 0x7fffffff;
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r) smin = min(smin, fstep[r] > s ? fstep[r] : 0x7fffffff);
+#pragma unroll
+            for (int dlt = kWave / 2; dlt > 0; dlt >>= 1) smin = min(smin, __shfl_xor(smin, dlt, kWave));
+            if (smin == 0x7fffffff) break;            // (nobody is running: cannot be, the batch has room then)
+            const double step_now = fma(cc.gamma, (double)C, fma(cc.beta, (double)n, cc.alpha));
+            if (d_first < 0.0) d_first = step_now;
+            const long long ks = smin - s;
+            // ks steps of a fixed batch: contexts grow by one per member and step
+            t += (double)ks * step_now + cc.gamma * ((double)n * (double)(ks * (ks - 1) / 2));
+            C += (long long)n * ks;
+            s = smin;
+            int gone = 0;
+            long long goneC = 0;
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r) {
+                if (fstep[r] == s) {
+                    const int i = r * kWave + lane;
+                    ++gone;
+                    goneC += cbase[r] + s;
+                    report(i, t, (double)olen[i], (double)octx[i]);
+                }
+            }
+            n -= wave_sum(gone);
+            C -= wave_sum(goneC);
+        }
+        // what is left, as of now: the sort words and contexts the closed form is built from
+        q = t;
+        Nrun = n;
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r) {
+            const int i = r * kWave + lane;
+            const bool running = fstep[r] > s && fstep[r] != 0x7fffffff;
+            key[r] = running ? ((uint32_t)(fstep[r] - s) << kIdxBits) | (uint32_t)i : 0xFFFFFFFFu;
+            if (running) ctx[i] = cbase[r] + s;
+        }
+    }
 
     bitonic_sort<kEPL>(key, lane);
 
@@ -202,7 +306,7 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     long long yl = 0, xl = 0, cl = 0;       // this lane's sums of R, c*R + tri(R), c
 #pragma unroll
     for (int r = 0; r < kEPL; ++r) {
-        const bool valid = lane * kEPL + r < N;
+        const bool valid = lane * kEPL + r < Nrun;
         idx[r] = (int)(key[r] & kIdxMask);
         R[r] = valid ? (int)(key[r] >> kIdxBits) : 0;
         cx[r] = valid ? ctx[idx[r]] : 0;
@@ -213,11 +317,6 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     long long Ytot, Xtot, Ctot;
     long long Y = wave_excl_scan(yl, Ytot), X = wave_excl_scan(xl, Xtot), Pc = wave_excl_scan(cl, Ctot);
 
-    // with a blend, every estimate below is keep * (white-box value) + lam * (Eq. 2 with the smoothed status)
-    const bool blended = a.lam != 0.0;
-    const double keep = 1.0 - a.lam;
-    const double bq = blended ? a.emaQ[g] : 0.0, bp = blended ? a.emaP[g] : 0.0, bd = blended ? a.emaD[g] : 0.0;
-
     // table entry v describes the segment after the v+1 shortest requests, n of them still running:
     //   E_g(L) = Gq + L * H + tri(L) * gamma * (n + 1)
     //   Gq = q + beta * Y + gamma * X,   H = alpha + beta * (n + 1) + gamma * S
@@ -226,12 +325,12 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
 #pragma unroll
     for (int r = 0; r < kEPL; ++r) {
         const int v = lane * kEPL + r;
-        const bool valid = v < N;
+        const bool valid = v < Nrun;
         const long long Rr = R[r], triR = (long long)(R[r] * (R[r] - 1) / 2);
         Y += Rr;
         X += (long long)cx[r] * Rr + triR;
         Pc += cx[r];
-        const double n_after = (double)(N - v - 1), S_next = (double)(Ctot - Pc);
+        const double n_after = (double)(Nrun - v - 1), S_next = (double)(Ctot - Pc);
         const double Yd = (double)Y, Xd = (double)X, Rd = (double)Rr;
         tR[r] = valid ? (uint16_t)R[r] : (uint16_t)0xFFFFu;
         double Gq = q + (cc.beta * Yd + cc.gamma * Xd);
@@ -242,15 +341,8 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
             // every product below is an integer below 2^53: exact
             const double I1 = Yd + n_after * Rd;
             const double I2 = Xd + Rd * S_next + n_after * (double)triR;
-            double fin = q + fma(cc.gamma, I2, fma(cc.beta, I1, cc.alpha * Rd));
-            if (blended)   // black-box finish: d per remaining token; a queued request also waits and prefills
-                fin = keep * fin + a.lam * (idx[r] < A ? bd * Rd : (bq + bp * (double)cx[r]) + bd * Rd);
-            if (idx[r] < A) {
-                a.out_act_finish[a0 + idx[r]] = (float)fin;
-                if (a.act_budget) a.out_flag[a0 + idx[r]] = fin > (double)a.act_budget[a0 + idx[r]];
-            } else if (a.out_q_finish && idx[r] < A + Q) {
-                a.out_q_finish[q0 + idx[r] - A] = (float)fin;
-            }
+            const double fin = q + fma(cc.gamma, I2, fma(cc.beta, I1, cc.alpha * Rd));
+            report(idx[r], fin, capped ? (double)olen[idx[r]] : Rd, capped ? (double)octx[idx[r]] : (double)cx[r]);
         }
     }
     {
@@ -278,13 +370,14 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     }
     if (lane == 0) {
         const double Cd = (double)Ctot;
-        double Gq0 = q, H0 = cc.alpha + (cc.beta * (double)(N + 1) + cc.gamma * Cd);
+        double Gq0 = q, H0 = cc.alpha + (cc.beta * (double)(Nrun + 1) + cc.gamma * Cd);
         if (blended) { Gq0 = keep * Gq0 + a.lam * bq; H0 = keep * H0 + a.lam * bd; }
         a.headGH[g] = make_float2((float)Gq0, (float)H0);
-        a.hN[g] = N;
+        a.hN[g] = Nrun;
         a.rank_acc[g] = 0;
         if (!a.use_pending) a.pend_cnt[g] = 0;
-        double d = fma(cc.gamma, Cd, fma(cc.beta, (double)N, cc.alpha));
+        // the next decode step that runs: the first one played above, else the batch as it stands
+        double d = d_first >= 0.0 ? d_first : fma(cc.gamma, Cd, fma(cc.beta, (double)Nrun, cc.alpha));
         if (blended) d = keep * d + a.lam * bd;
         a.hD[g] = d;
         if (a.out_d) a.out_d[g] = d;
@@ -393,8 +486,10 @@ __global__ __launch_bounds__(kBlock) void k_commit(int64_t n, const int* __restr
 template <int kEPL>
 void launch_build(const BuildArgs& b, int M, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_build<kEPL>, dim3((M + kBuildWaves - 1) / kBuildWaves), dim3(kBlock),
-                       (size_t)kBuildWaves * kWave * kEPL * sizeof(int), s, b);
+    const dim3 grid((M + kBuildWaves - 1) / kBuildWaves);
+    const size_t lds = (size_t)kBuildWaves * 3 * kWave * kEPL * sizeof(int);
+    if (b.batch_cap) hipLaunchKernelGGL((k_build<kEPL, true>), grid, dim3(kBlock), lds, s, b);
+    else hipLaunchKernelGGL((k_build<kEPL, false>), grid, dim3(kBlock), lds, s, b);
 }
 
 }  // namespace
@@ -432,6 +527,7 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
     b.n_inst = f->n_inst; b.max_entries = f->max_entries; b.max_len = f->max_len;
     b.pend_cnt = f->pend_cnt; b.pend_prompt = f->pend_prompt; b.pend_len = f->pend_len;
     b.use_pending = in.use_pending;
+    b.batch_cap = f->has_cap ? f->batch_cap : nullptr;
     b.lam = f->lam; b.emaQ = f->emaQ; b.emaP = f->emaP; b.emaD = f->emaD;
     const int M = f->n_inst;
     {

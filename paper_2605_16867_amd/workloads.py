@@ -247,3 +247,13 @@ def observed_status(fl: Fleet, rounds: int = 3, seed: int = 0):
         decode = ((fl.coef["alpha"][c] + fl.coef["beta"][c] * n_g) * rng.lognormal(0.0, 0.3, M)).astype(np.float32)
         out.append((0.3, wait, prefill, decode))
     return out
+
+
+def batch_caps(fl: Fleet, lo: float = 0.5, hi: float = 1.2, seed: int = 0) -> np.ndarray:
+    """A cap on the requests each instance may decode together (the paper's memory
+    constraint, Sec. 3.1, for which it gives no figures): the instance's current number
+    of requests (running + queued) times a factor uniform in [lo, hi], at least 1.
+    Factors below 1 make the queue wait; above 1 the cap does not bind."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    n_g = (np.diff(fl.act_off) + np.diff(fl.q_off)).astype(np.float64)
+    return np.maximum(1, np.rint(n_g * rng.uniform(lo, hi, fl.n_inst))).astype(np.int32)

@@ -142,6 +142,8 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
     M = len(fl.inst_class)
     na, nq, R = len(fl.act_prompt), len(fl.q_prompt), len(fl.in_prompt)
     h = make_handle(fl)
+    if getattr(fl, "batch_cap", None) is not None:
+        h.gr_set_batch_cap(fl.batch_cap)
     rng = np.random.default_rng(seed)
     view = lambda s, rem=None: s
     if blackbox is not None:
@@ -259,7 +261,9 @@ def run_feedback_and_check(fl, chunk: int, n_req: Optional[int] = None, exclude=
     R = len(fl.in_prompt) if n_req is None else n_req
     c0, ln, D32 = fl.in_prompt[:R], fl.in_len[:R], fl.in_budget[:R]
     me = int(max(np.diff(fl.act_off) + np.diff(fl.q_off)))
-    h = make_handle(fl, max_requests=max(R, 1), max_entries=min(me + R, 2048))
+    h = make_handle(fl, max_requests=max(R, 256), max_entries=min(me + R, 2048))
+    if getattr(fl, "batch_cap", None) is not None:
+        h.gr_set_batch_cap(fl.batch_cap)
     na = len(fl.act_prompt)
     fin = torch.zeros(na, dtype=torch.float32, device=dev)
     h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"],

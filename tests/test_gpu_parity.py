@@ -181,3 +181,42 @@ def test_feedback_routing_large_fleet_with_exclusions():
     ex = np.random.default_rng(4).integers(-1, fl.n_inst, 1024).astype(np.int32)
     rep = parity.run_feedback_and_check(fl, 128, n_req=1024, exclude=ex)
     report("feedback large", rep)
+
+
+# --------------------------------------------------------------------------- batch cap (Sec. 3.1's memory bound)
+@pytest.mark.parametrize("lo,hi", [(0.3, 1.2), (0.9, 1.0), (1.0, 1.0)])
+def test_mid_fleet_with_batch_caps(lo, hi):
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=3.0, occupancy_jitter=True, seed=51))
+    fl.batch_cap = workloads.batch_caps(fl, lo, hi, seed=1)
+    rep = parity.run_and_check(fl)
+    report(f"mid caps {lo}-{hi}", rep)
+
+
+def test_batch_caps_with_everything_else():
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=2.0, seed=52))
+    fl.batch_cap = workloads.batch_caps(fl, 0.4, 1.1, seed=2)
+    hits = workloads.cached_prefixes(fl, mean_hits=3.0, seed=7)
+    ex = np.random.default_rng(5).integers(-1, fl.n_inst, len(fl.in_prompt)).astype(np.int32)
+    rep = parity.run_and_check(fl, exclude=ex, hits=hits, blackbox=(workloads.observed_status(fl, 2, seed=5), 0.4))
+    report("mid caps + prefixes + exclude + blend", rep)
+
+
+def test_tiny_fleet_with_queue_heavy_caps():
+    fl = workloads.make_fleet(workloads.spec("tiny", n_queued=40, slo_scale=6.0, seed=53))
+    for cap in (1, 7, 64, 103, 104, 105):
+        fl.batch_cap = np.full(fl.n_inst, cap, dtype=np.int32)
+        report(f"tiny cap {cap}", parity.run_and_check(fl))
+
+
+def test_heavy_fleet_with_batch_caps_sampled():
+    fl = workloads.make_fleet(workloads.spec("heavy", n_incoming=65536))
+    fl.batch_cap = workloads.batch_caps(fl, 0.8, 1.1, seed=3)
+    rep = parity.run_and_check(fl, sample=1024)
+    report("heavy caps", rep)
+
+
+def test_feedback_routing_with_batch_caps_request_by_request():
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=3.0, seed=54))
+    fl.batch_cap = workloads.batch_caps(fl, 0.7, 1.05, seed=4)
+    rep = parity.run_feedback_and_check(fl, 1, n_req=200)
+    report("feedback caps chunk 1", rep)
