@@ -287,8 +287,12 @@ int gr_device_status(gr_fleet* f, int32_t* out_bits);
  * number of launches per kernel id since the last read into HOST arrays of
  * n_kernels entries, and forgets them.  Kernel ids run from 0 to
  * gr_profile_kernel_count() - 1; gr_profile_kernel_name gives a static name.
+ * gr_profile_select restricts the timing to the kernel ids whose bit is set in
+ * kernel_mask (all of them after gr_create): an event pair costs a few
+ * microseconds of stream time, which adds up over a dozen short launches.
  */
 int gr_profile_enable(gr_fleet* f, int32_t max_launches);
+int gr_profile_select(gr_fleet* f, uint64_t kernel_mask);
 int gr_profile_read(gr_fleet* f, int32_t n_kernels, double* total_ms, int64_t* launches);
 int32_t gr_profile_kernel_count(void);
 const char* gr_profile_kernel_name(int32_t id);

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libgoodroute.so")
 
 EXPORTS = ("gr_create", "gr_destroy", "gr_build_status", "gr_score_route", "gr_score_route_cached", "gr_route_feedback",
            "gr_risk_scan", "gr_observe", "gr_set_blend", "gr_set_batch_cap",
-           "gr_device_status", "gr_strerror", "gr_profile_enable", "gr_profile_read",
+           "gr_device_status", "gr_strerror", "gr_profile_enable", "gr_profile_select", "gr_profile_read",
            "gr_profile_kernel_count", "gr_profile_kernel_name")
 
 _lib = None
@@ -58,6 +58,8 @@ def lib() -> C.CDLL:
         l.gr_device_status.argtypes = [p, C.POINTER(i32)]
         l.gr_profile_enable.restype = C.c_int
         l.gr_profile_enable.argtypes = [p, i32]
+        l.gr_profile_select.restype = C.c_int
+        l.gr_profile_select.argtypes = [p, C.c_uint64]
         l.gr_profile_read.restype = C.c_int
         l.gr_profile_read.argtypes = [p, i32, p, p]
         l.gr_profile_kernel_count.restype = i32
@@ -211,6 +213,16 @@ class Fleet:
 
     def gr_profile_enable(self, max_launches: int) -> None:
         _check(lib().gr_profile_enable(self._h, int(max_launches)), "gr_profile_enable")
+
+    def gr_profile_select(self, names=None) -> None:
+        """Time only the kernels whose name starts with one of `names` (None: all)."""
+        n = int(lib().gr_profile_kernel_count())
+        mask = 0
+        for k in range(n):
+            nm = lib().gr_profile_kernel_name(k).decode()
+            if names is None or any(nm.startswith(x) for x in names):
+                mask |= 1 << k
+        _check(lib().gr_profile_select(self._h, mask), "gr_profile_select")
 
     def gr_profile_read(self) -> dict:
         """{kernel name: (total milliseconds, launches)} since the last read."""

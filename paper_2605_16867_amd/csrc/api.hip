@@ -303,6 +303,13 @@ int gr_profile_enable(gr_fleet* f, int32_t max_launches)
     return GR_OK;
 }
 
+int gr_profile_select(gr_fleet* f, uint64_t kernel_mask)
+{
+    if (!f) return GR_ERR_INVALID_ARG;
+    f->prof.mask = kernel_mask;
+    return GR_OK;
+}
+
 int gr_profile_read(gr_fleet* f, int32_t n_kernels, double* total_ms, int64_t* launches)
 {
     if (!f || n_kernels < 0 || (n_kernels > 0 && (!total_ms || !launches))) return GR_ERR_INVALID_ARG;

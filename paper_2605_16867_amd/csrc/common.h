@@ -37,8 +37,9 @@ constexpr int kMaxEntries = 2048;
 constexpr int kMaxClasses = 64;
 constexpr int kMaxLen = 32767;     // one LDS counter per length in the grouping kernels
 constexpr int kTileReq = 32;       // requests of one length scored together by one wave
-constexpr int kGroupItems = 16;    // requests per thread in the grouping kernels
-constexpr int kGroupChunk = kBlock * kGroupItems;
+constexpr int kGroupBlock = 1024;  // threads per workgroup of the grouping kernels (their cost is the pass over the LDS bins)
+constexpr int kGroupItems = 4;     // requests per thread in the grouping kernels
+constexpr int kGroupChunk = kGroupBlock * kGroupItems;
 constexpr int kMemoU = 256;        // lengths per pass of a workgroup of the memo kernel
 constexpr int kMemoP = 16;         // instances (waves) per workgroup of the memo kernel
 
@@ -81,6 +82,7 @@ enum KernelId {
 
 struct Profiler {
     bool on = false;
+    uint64_t mask = ~0ull;           // bit k: launches of kernel id k are timed
     std::vector<hipEvent_t> events;  // pairs: start, stop
     std::vector<int> ids;            // kernel id of each recorded pair
 };
@@ -162,7 +164,7 @@ struct ProfScope {
     size_t slot = SIZE_MAX;
     ProfScope(gr_fleet* f, int id, hipStream_t stream) : p(f->prof), s(stream)
     {
-        if (!p.on || (p.ids.size() + 1) * 2 > p.events.size()) return;
+        if (!p.on || !((p.mask >> id) & 1ull) || (p.ids.size() + 1) * 2 > p.events.size()) return;
         slot = p.ids.size();
         p.ids.push_back(id);
         (void)hipEventRecord(p.events[2 * slot], s);

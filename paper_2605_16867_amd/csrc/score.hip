@@ -38,23 +38,23 @@ __device__ inline bool fetch_len(const ReqSrc& s, int64_t i, int max_len, int& L
 // counters per word: a workgroup sees at most kGroupChunk requests), then one
 // global atomic per length the workgroup has seen.
 template <bool kMigrate>
-__global__ __launch_bounds__(kBlock) void k_hist(ReqSrc s, int* __restrict__ len_cnt, int bins, int max_len)
+__global__ __launch_bounds__(kGroupBlock) void k_hist(ReqSrc s, int* __restrict__ len_cnt, int bins, int max_len)
 {
     extern __shared__ uint32_t lds[];
     const int tid = threadIdx.x;
     const int nwords = (bins + 1) / 2;
-    for (int w = tid; w < nwords; w += kBlock) lds[w] = 0;
+    for (int w = tid; w < nwords; w += kGroupBlock) lds[w] = 0;
     __syncthreads();
     const int64_t base = (int64_t)blockIdx.x * kGroupChunk;
 #pragma unroll
     for (int it = 0; it < kGroupItems; ++it) {
-        const int64_t i = base + it * kBlock + tid;
+        const int64_t i = base + it * kGroupBlock + tid;
         int L;
         if (i < s.n && fetch_len<kMigrate>(s, i, max_len, L))
             atomicAdd(&lds[L >> 1], (L & 1) ? 0x10000u : 1u);
     }
     __syncthreads();
-    for (int w = tid; w < nwords; w += kBlock) {
+    for (int w = tid; w < nwords; w += kGroupBlock) {
         const uint32_t v = lds[w];
         if (v & 0xFFFFu) atomicAdd(&len_cnt[2 * w], (int)(v & 0xFFFFu));
         if (v >> 16) atomicAdd(&len_cnt[2 * w + 1], (int)(v >> 16));
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, 
 // Requests into grouped order.  Per workgroup: count per length in LDS, reserve
 // that many slots of each length with one global atomic, hand the slots out.
 template <bool kMigrate>
-__global__ __launch_bounds__(kBlock) void k_scatter(ReqSrc s, int* __restrict__ len_base,
+__global__ __launch_bounds__(kGroupBlock) void k_scatter(ReqSrc s, int* __restrict__ len_base,
                                                     const int* __restrict__ rank, ReqRec* __restrict__ recs,
                                                     int* __restrict__ out_inst, float* __restrict__ out_slack,
                                                     int bins, int max_len, int n_inst)
@@ -145,13 +145,13 @@ __global__ __launch_bounds__(kBlock) void k_scatter(ReqSrc s, int* __restrict__ 
     extern __shared__ uint32_t lds[];
     int* slot = reinterpret_cast<int*>(lds);
     const int tid = threadIdx.x;
-    for (int L = tid; L < bins; L += kBlock) slot[L] = 0;
+    for (int L = tid; L < bins; L += kGroupBlock) slot[L] = 0;
     __syncthreads();
     const int64_t base = (int64_t)blockIdx.x * kGroupChunk;
     int Ls[kGroupItems];
 #pragma unroll
     for (int it = 0; it < kGroupItems; ++it) {
-        const int64_t i = base + it * kBlock + tid;
+        const int64_t i = base + it * kGroupBlock + tid;
         int L = -1;
         if (i < s.n) {
             if (fetch_len<kMigrate>(s, i, max_len, L)) {
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kBlock) void k_scatter(ReqSrc s, int* __restrict__ 
         Ls[it] = L;
     }
     __syncthreads();
-    for (int L = tid; L < bins; L += kBlock) {
+    for (int L = tid; L < bins; L += kGroupBlock) {
         const int c = slot[L];
         if (c) slot[L] = atomicAdd(&len_base[L], c);
     }
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kBlock) void k_scatter(ReqSrc s, int* __restrict__ 
     for (int it = 0; it < kGroupItems; ++it) {
         const int L = Ls[it];
         if (L < 0) continue;
-        const int64_t i = base + it * kBlock + tid;
+        const int64_t i = base + it * kGroupBlock + tid;
         const int pos = atomicAdd(&slot[L], 1);
         int c0, ex;
         float D;
@@ -827,8 +827,8 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     const int off = migrate ? kHistMigrate - kHistRoute : 0;
     {
         ProfScope ps(f, kHistRoute + off, s);
-        if (migrate) hipLaunchKernelGGL(k_hist<true>, dim3(g_blocks), dim3(kBlock), hist_lds, s, src, f->len_cnt, bins, f->max_len);
-        else hipLaunchKernelGGL(k_hist<false>, dim3(g_blocks), dim3(kBlock), hist_lds, s, src, f->len_cnt, bins, f->max_len);
+        if (migrate) hipLaunchKernelGGL(k_hist<true>, dim3(g_blocks), dim3(kGroupBlock), hist_lds, s, src, f->len_cnt, bins, f->max_len);
+        else hipLaunchKernelGGL(k_hist<false>, dim3(g_blocks), dim3(kGroupBlock), hist_lds, s, src, f->len_cnt, bins, f->max_len);
     }
     {
         ProfScope ps(f, kScanRoute + off, s);
@@ -837,9 +837,9 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     }
     {
         ProfScope ps(f, kScatterRoute + off, s);
-        if (migrate) hipLaunchKernelGGL(k_scatter<true>, dim3(g_blocks), dim3(kBlock), scat_lds, s, src, f->len_base,
+        if (migrate) hipLaunchKernelGGL(k_scatter<true>, dim3(g_blocks), dim3(kGroupBlock), scat_lds, s, src, f->len_base,
                                         f->rank, f->recs, out.inst, out.slack, bins, f->max_len, f->n_inst);
-        else hipLaunchKernelGGL(k_scatter<false>, dim3(g_blocks), dim3(kBlock), scat_lds, s, src, f->len_base,
+        else hipLaunchKernelGGL(k_scatter<false>, dim3(g_blocks), dim3(kGroupBlock), scat_lds, s, src, f->len_base,
                                 f->rank, f->recs, out.inst, out.slack, bins, f->max_len, f->n_inst);
     }
     const int64_t max_rows = n < bins ? n : bins;
