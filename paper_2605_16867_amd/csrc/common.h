@@ -38,8 +38,6 @@ constexpr int kMaxClasses = 64;
 constexpr int kMaxLen = 32767;     // one LDS counter per length in the grouping kernels
 constexpr int kTileReq = 32;       // requests of one length scored together by one wave
 constexpr int kGroupBlock = 1024;  // threads per workgroup of the grouping kernels (their cost is the pass over the LDS bins)
-constexpr int kGroupItems = 4;     // requests per thread in the grouping kernels
-constexpr int kGroupChunk = kGroupBlock * kGroupItems;
 constexpr int kMemoU = 256;        // lengths per pass of a workgroup of the memo kernel
 constexpr int kMemoP = 16;         // instances (waves) per workgroup of the memo kernel
 

@@ -35,9 +35,9 @@ __device__ inline bool fetch_len(const ReqSrc& s, int64_t i, int max_len, int& L
 
 // ------------------------------------------------------------------ grouping by length
 // Requests per length: a histogram private to the workgroup in LDS (two 16-bit
-// counters per word: a workgroup sees at most kGroupChunk requests), then one
+// counters per word: a workgroup sees at most 1024 * kItems < 65536 requests), then one
 // global atomic per length the workgroup has seen.
-template <bool kMigrate>
+template <bool kMigrate, int kItems>
 __global__ __launch_bounds__(kGroupBlock) void k_hist(ReqSrc s, int* __restrict__ len_cnt, int bins, int max_len)
 {
     extern __shared__ uint32_t lds[];
@@ -45,9 +45,9 @@ __global__ __launch_bounds__(kGroupBlock) void k_hist(ReqSrc s, int* __restrict_
     const int nwords = (bins + 1) / 2;
     for (int w = tid; w < nwords; w += kGroupBlock) lds[w] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kGroupChunk;
+    const int64_t base = (int64_t)blockIdx.x * (kGroupBlock * kItems);
 #pragma unroll
-    for (int it = 0; it < kGroupItems; ++it) {
+    for (int it = 0; it < kItems; ++it) {
         const int64_t i = base + it * kGroupBlock + tid;
         int L;
         if (i < s.n && fetch_len<kMigrate>(s, i, max_len, L))
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, 
 
 // Requests into grouped order.  Per workgroup: count per length in LDS, reserve
 // that many slots of each length with one global atomic, hand the slots out.
-template <bool kMigrate>
+template <bool kMigrate, int kItems>
 __global__ __launch_bounds__(kGroupBlock) void k_scatter(ReqSrc s, int* __restrict__ len_base,
                                                     const int* __restrict__ rank, ReqRec* __restrict__ recs,
                                                     int* __restrict__ out_inst, float* __restrict__ out_slack,
@@ -147,10 +147,10 @@ __global__ __launch_bounds__(kGroupBlock) void k_scatter(ReqSrc s, int* __restri
     const int tid = threadIdx.x;
     for (int L = tid; L < bins; L += kGroupBlock) slot[L] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kGroupChunk;
-    int Ls[kGroupItems];
+    const int64_t base = (int64_t)blockIdx.x * (kGroupBlock * kItems);
+    int Ls[kItems];
 #pragma unroll
-    for (int it = 0; it < kGroupItems; ++it) {
+    for (int it = 0; it < kItems; ++it) {
         const int64_t i = base + it * kGroupBlock + tid;
         int L = -1;
         if (i < s.n) {
@@ -171,7 +171,7 @@ __global__ __launch_bounds__(kGroupBlock) void k_scatter(ReqSrc s, int* __restri
     }
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < kGroupItems; ++it) {
+    for (int it = 0; it < kItems; ++it) {
         const int L = Ls[it];
         if (L < 0) continue;
         const int64_t i = base + it * kGroupBlock + tid;
@@ -808,8 +808,9 @@ size_t score_lds_bytes(const gr_fleet* f)
 int score_prepare(gr_fleet* f)
 {
     const size_t hist = (size_t)((f->bins + 1) / 2) * 4, scat = (size_t)f->bins * 4;
-    const bool ok = set_lds(k_hist<false>, hist) && set_lds(k_hist<true>, hist) &&
-                    set_lds(k_scatter<false>, scat) && set_lds(k_scatter<true>, scat) &&
+    const bool ok = set_lds(k_hist<false, 4>, hist) && set_lds(k_hist<true, 4>, hist) &&
+                    set_lds(k_hist<false, 16>, hist) && set_lds(k_hist<true, 16>, hist) &&
+                    set_lds(k_scatter<false, 4>, scat) && set_lds(k_scatter<true, 4>, scat) &&
                     set_lds(k_scan, scat) && set_lds(k_memo, memo_lds_bytes(f));
     return ok ? GR_OK : GR_ERR_HIP;
 }
@@ -822,13 +823,21 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
     }
     const int bins = f->bins;
-    const unsigned g_blocks = (unsigned)((n + kGroupChunk - 1) / kGroupChunk);
+    // requests per workgroup of the grouping kernels.  Every workgroup pays a pass over all length
+    // bins and one global atomic per length it has seen: the histogram of a large batch is faster
+    // with few large workgroup shares, the scatter (which also writes the records) is not.
+    const int h_items = n > (int64_t(1) << 20) ? 16 : 4, s_items = 4;
+    const auto blocks_for = [n](int items) {
+        return (unsigned)((n + (int64_t)kGroupBlock * items - 1) / ((int64_t)kGroupBlock * items));
+    };
     const size_t hist_lds = (size_t)((bins + 1) / 2) * 4, scat_lds = (size_t)bins * 4;
     const int off = migrate ? kHistMigrate - kHistRoute : 0;
     {
         ProfScope ps(f, kHistRoute + off, s);
-        if (migrate) hipLaunchKernelGGL(k_hist<true>, dim3(g_blocks), dim3(kGroupBlock), hist_lds, s, src, f->len_cnt, bins, f->max_len);
-        else hipLaunchKernelGGL(k_hist<false>, dim3(g_blocks), dim3(kGroupBlock), hist_lds, s, src, f->len_cnt, bins, f->max_len);
+#define GR_LAUNCH_HIST(M, I) hipLaunchKernelGGL((k_hist<M, I>), dim3(blocks_for(I)), dim3(kGroupBlock), hist_lds, s, src, f->len_cnt, bins, f->max_len)
+        if (migrate) { if (h_items == 16) GR_LAUNCH_HIST(true, 16); else GR_LAUNCH_HIST(true, 4); }
+        else { if (h_items == 16) GR_LAUNCH_HIST(false, 16); else GR_LAUNCH_HIST(false, 4); }
+#undef GR_LAUNCH_HIST
     }
     {
         ProfScope ps(f, kScanRoute + off, s);
@@ -837,10 +846,11 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     }
     {
         ProfScope ps(f, kScatterRoute + off, s);
-        if (migrate) hipLaunchKernelGGL(k_scatter<true>, dim3(g_blocks), dim3(kGroupBlock), scat_lds, s, src, f->len_base,
-                                        f->rank, f->recs, out.inst, out.slack, bins, f->max_len, f->n_inst);
-        else hipLaunchKernelGGL(k_scatter<false>, dim3(g_blocks), dim3(kGroupBlock), scat_lds, s, src, f->len_base,
-                                f->rank, f->recs, out.inst, out.slack, bins, f->max_len, f->n_inst);
+#define GR_LAUNCH_SCATTER(M, I) hipLaunchKernelGGL((k_scatter<M, I>), dim3(blocks_for(I)), dim3(kGroupBlock), scat_lds, s, src, \
+                                                   f->len_base, f->rank, f->recs, out.inst, out.slack, bins, f->max_len, f->n_inst)
+        (void)s_items;
+        if (migrate) GR_LAUNCH_SCATTER(true, 4); else GR_LAUNCH_SCATTER(false, 4);
+#undef GR_LAUNCH_SCATTER
     }
     const int64_t max_rows = n < bins ? n : bins;
     {
