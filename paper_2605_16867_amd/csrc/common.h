@@ -148,6 +148,7 @@ struct gr_fleet {
     int* row_off = nullptr;   // [row_cap+1] first request of each distinct length
     int* tile_off = nullptr;  // [row_cap+1] first tile of each distinct length
     int* len_row = nullptr;   // [bins] row of each length present in the last batch
+    int* len_ceil = nullptr;  // [bins] rows shorter than each length = the first row at least that long
     int* totals = nullptr;    // [4] requests, distinct lengths, tiles
     gr::ReqRec* recs = nullptr;  // [req_cap] requests in grouped order
     float* memo = nullptr;       // [row_cap][m_pad] E per distinct length and position

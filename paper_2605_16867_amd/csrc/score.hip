@@ -92,7 +92,8 @@ __device__ inline unsigned long long block_incl_scan(unsigned long long v, unsig
 __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, int* __restrict__ len_base,
                                                      int* __restrict__ row_len, int* __restrict__ row_off,
                                                      int* __restrict__ tile_off, int* __restrict__ len_row,
-                                                     int* __restrict__ totals, int* __restrict__ out_n, int bins)
+                                                     int* __restrict__ len_ceil, int* __restrict__ totals,
+                                                     int* __restrict__ out_n, int bins)
 {
     extern __shared__ uint32_t lds[];
     int* cnt = reinterpret_cast<int*>(lds);
@@ -114,6 +115,7 @@ __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, 
     for (int i = i0; i < i1; ++i) {
         const unsigned c = (unsigned)cnt[i];
         cnt[i] = (int)(run & 0xFFFFFFFFull);
+        len_ceil[i] = u;          // rows shorter than i = the first row that is at least i long
         if (c) {
             len_row[i] = u;
             row_len[u] = i;
@@ -193,7 +195,7 @@ __global__ __launch_bounds__(kGroupBlock) void k_scatter(ReqSrc s, int* __restri
 
 // ------------------------------------------------------------------ closed-form lookups
 struct MemoArgs {
-    const int *totals, *row_len, *order, *hN;
+    const int *totals, *row_len, *len_ceil, *order, *hN;
     const ClassCoef* cls;
     const int* inst_class;
     const uint16_t* tabR;
@@ -204,15 +206,20 @@ struct MemoArgs {
 };
 
 // E of every (distinct length, instance).  A workgroup of kMemoP waves takes
-// kMemoP consecutive positions of the capability order, one instance per wave:
-// the wave copies the instance's sorted lengths to LDS once, then walks the
-// distinct lengths kMemoU at a time; a lane takes a length, finds its segment
-// k = #{R_i <= L} by binary search in LDS and evaluates the segment's quadratic
-// (the coefficients of neighbouring lengths share cache lines).  Each pass is
-// turned in LDS, in one of two buffers so that one barrier per pass is enough,
-// and written in runs of kMemoP positions per length.
+// kMemoP consecutive positions of the capability order, one instance per wave,
+// and a run of consecutive distinct lengths ("rows", ascending), kMemoU at a
+// time.  The segment of a length is k = #{R_i <= L}.  Both the instance's
+// lengths R and the rows are sorted, so k is found by counting instead of
+// searching: the instance's entries that fall between the previous pass's last
+// row and this pass's last row (a handful) each add one to the counter of the
+// first row that is at least as long (a table over all lengths from the
+// grouping pass), and a prefix sum over the pass's counters, carried from pass
+// to pass, gives k for every row.  Each pass is turned in LDS, in one of two
+// buffers so that one barrier per pass is enough, and written in runs of kMemoP
+// positions per length.
 constexpr int kMemoBlock = kMemoP * kWave;
 constexpr int kMemoTile = kMemoU * (kMemoP + 1);       // floats
+static_assert(kMemoU == 4 * kWave, "a lane owns four consecutive counters");
 
 __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
 {
@@ -221,10 +228,14 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
     const int U = a.totals[1];
     const int p0 = blockIdx.x * kMemoP;
     const int tid = threadIdx.x, lane = lane_id(), pi = tid / kWave;
-    uint16_t* sR = reinterpret_cast<uint16_t*>(tiles + 2 * kMemoTile) + (size_t)pi * a.cap;
+    int* cnt = reinterpret_cast<int*>(tiles + 2 * kMemoTile) + pi * kMemoU;
+    uint16_t* sR = reinterpret_cast<uint16_t*>(tiles + 2 * kMemoTile + kMemoP * kMemoU) + (size_t)pi * a.cap;
     constexpr int kPerLane = kMemoU / kWave;
     const int p = p0 + pi;
     const int g = p < a.n_inst ? a.order[p] : -1;
+    // this workgroup's run of rows
+    const int per = ((U + (int)gridDim.y - 1) / (int)gridDim.y + kMemoU - 1) / kMemoU * kMemoU;
+    const int ub = blockIdx.y * per, ue = min(ub + per, U);
     int N = 0;
     float2 head = make_float2(0.f, 0.f);
     float gam = 0.f;
@@ -241,32 +252,55 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
+    // entries not longer than the row before the run: the one search of this wave (every lane the same)
+    int kb = 0;
+    if (g >= 0 && ub > 0 && ub < ue) {
+        const int Lprev = a.row_len[ub - 1];
+        for (int step = a.cap; step >= 1; step >>= 1) {
+            const int probe = kb + step;
+            if (probe <= N && (int)sR[probe - 1] <= Lprev) kb = probe;
+        }
+    }
+
     int buf = 0;
-    for (int u0 = blockIdx.y * kMemoU; u0 < U; u0 += gridDim.y * kMemoU, buf ^= 1) {
+    for (int u0 = ub; u0 < ue; u0 += kMemoU, buf ^= 1) {
         float* tile = tiles + buf * kMemoTile;
         if (g >= 0) {
-            int Lv[kPerLane], kk[kPerLane];
+            reinterpret_cast<int4*>(cnt)[lane] = make_int4(0, 0, 0, 0);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const int Lhi = a.row_len[min(u0 + kMemoU, U) - 1];
+            int taken = 0;
+            for (int e = kb + lane;; e += kWave) {       // the lanes that still find an entry form a prefix
+                const bool ok = e < N && (int)sR[min(e, N - 1)] <= Lhi && N > 0;
+                if (ok) atomicAdd(&cnt[a.len_ceil[sR[e]] - u0], 1);
+                const unsigned long long m = __ballot(ok);
+                taken += __popcll(m);
+                if (m != ~0ull) break;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            int4 c = reinterpret_cast<int4*>(cnt)[lane];      // rows 4 lane .. 4 lane + 3 of the pass
+            c.y += c.x; c.z += c.y; c.w += c.z;
+            const int before = kb + wave_incl_scan(c.w) - c.w;
+            c.x += before; c.y += before; c.z += before; c.w += before;
+            reinterpret_cast<int4*>(cnt)[lane] = c;           // now k of each row
+            kb += taken;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
             for (int i = 0; i < kPerLane; ++i) {
-                const int u = u0 + lane + kWave * i;
-                Lv[i] = u < U ? a.row_len[u] : 0;
-                kk[i] = 0;
-            }
-            // largest k <= N with R_k <= L (R_1 <= R_2 <= ..), the same number of probes for every lane
-            for (int step = a.cap; step >= 1; step >>= 1) {
-#pragma unroll
-                for (int i = 0; i < kPerLane; ++i) {
-                    const int probe = kk[i] + step;
-                    if (probe <= N && (int)sR[probe - 1] <= Lv[i]) kk[i] = probe;
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < kPerLane; ++i) {
+                const int row = lane + kWave * i, u = u0 + row;
+                const int k = cnt[row];
+                const int L = u < U ? a.row_len[u] : 0;
                 float2 gh = head;
-                if (kk[i] > 0) gh = GH[kk[i] - 1];
-                const float Lf = (float)Lv[i];
+                if (k > 0) gh = GH[k - 1];
+                const float Lf = (float)L;
                 const float tri = Lf * (Lf - 1.0f) * 0.5f;
-                tile[(lane + kWave * i) * (kMemoP + 1) + pi] = fmaf(Lf, gh.y, gh.x) + tri * (gam * (float)(N - kk[i] + 1));
+                tile[row * (kMemoP + 1) + pi] = fmaf(Lf, gh.y, gh.x) + tri * (gam * (float)(N - k + 1));
             }
         } else {
 #pragma unroll
@@ -797,7 +831,10 @@ bool set_lds(K kernel, size_t bytes)
 
 }  // namespace
 
-size_t memo_lds_bytes(const gr_fleet* f) { return sizeof(float) * 2 * kMemoTile + (size_t)kMemoP * f->cap * 2; }
+size_t memo_lds_bytes(const gr_fleet* f)
+{
+    return sizeof(float) * 2 * kMemoTile + sizeof(int) * kMemoP * kMemoU + (size_t)kMemoP * f->cap * 2;
+}
 
 size_t score_lds_bytes(const gr_fleet* f)
 {
@@ -842,7 +879,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     {
         ProfScope ps(f, kScanRoute + off, s);
         hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanBlock), scat_lds, s, f->len_cnt, f->len_base, f->row_len,
-                           f->row_off, f->tile_off, f->len_row, f->totals, out.n_selected, bins);
+                           f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, out.n_selected, bins);
     }
     {
         ProfScope ps(f, kScatterRoute + off, s);
@@ -855,7 +892,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     const int64_t max_rows = n < bins ? n : bins;
     {
         MemoArgs m{};
-        m.totals = f->totals; m.row_len = f->row_len; m.order = f->order; m.hN = f->hN;
+        m.totals = f->totals; m.row_len = f->row_len; m.len_ceil = f->len_ceil; m.order = f->order; m.hN = f->hN;
         m.cls = f->cls; m.inst_class = f->inst_class;
         m.tabR = f->tabR; m.tabGH = f->tabGH; m.headGH = f->headGH; m.memo = f->memo;
         m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.cap = f->cap; m.keep = (float)(1.0 - f->lam_built);
