@@ -572,6 +572,44 @@ __device__ inline void exact_choice(const RowView& rv, float c0, float D, int pe
     val = bp >= 0 ? Tm : 0.f;
 }
 
+// Main pass of a tile: T = E + c0 * kappa for the first kN requests against every
+// position, folded into each request's running minimum per lane.  Two blocks
+// of 64 positions per step, the operands of the next step in flight (two
+// register sets taking turns, so that nothing is copied).
+template <int kN>
+__device__ __forceinline__ void main_pass(const RowView& rv, const float (&c0)[kTileReq], float (&minT)[kTileReq],
+                                          int lane)
+{
+    struct Step { float Ea, Eb; float2 Ka, Kb; };
+    auto fetch = [&](Step& st, int b) {
+        st.Ea = rv.E[b * kWave + lane]; st.Eb = rv.E[(b + 1) * kWave + lane];
+        st.Ka = rv.posK[b * kWave + lane]; st.Kb = rv.posK[(b + 1) * kWave + lane];
+    };
+    auto fold = [&](const Step& st) {
+        const float ka = kappa_of(st.Ka, rv.Lf), kb = kappa_of(st.Kb, rv.Lf);
+#pragma unroll
+        for (int j = 0; j < kN; ++j) {
+            const float Ta = fmaf(c0[j], ka, st.Ea), Tb = fmaf(c0[j], kb, st.Eb);
+            minT[j] = fminf(fminf(minT[j], Ta), Tb);
+        }
+    };
+    // the prefetch is unconditional (past the end it re-reads the last step), so that the
+    // compiler can count exactly how many loads may stay in flight at each use
+    Step s0, s1;
+    const int last = rv.nblk - 2;
+    fetch(s0, 0);
+    for (int b = 0; b < rv.nblk; b += 4) {
+        fetch(s1, min(b + 2, last));
+        __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the arithmetic
+        fold(s0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(s0, min(b + 4, last));
+        __builtin_amdgcn_sched_barrier(0);
+        if (b + 2 < rv.nblk) fold(s1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 constexpr int kSparseFeasible = 8;   // up to this many feasible requests of a tile go one by one
 
 // One wave per tile: up to kTileReq requests of one length against all
@@ -586,18 +624,29 @@ constexpr int kSparseFeasible = 8;   // up to this many feasible requests of a t
 // one (the just-enough choice).  The others take the instance of the minimum,
 // found by recomputing the positions of the lane that holds it (the earliest
 // position in capability order among equal minima).
-template <bool kWriteT>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tile(TileArgs a)
+//
+// kW waves per workgroup.  With kW > 4 the workgroup first copies the (delta,
+// gamma) pairs of all positions, which every tile reads in full, into LDS:
+// 32 / kW workgroups of m_pad * 8 bytes share a compute unit, and the texture
+// path is left to the table rows and the gathers of the search for the minimum.
+template <bool kWriteT, int kW>
+__global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tile(TileArgs a)
 {
+    constexpr bool kLdsK = kW > 4;
+    extern __shared__ float2 lds_posK[];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int NT = a.totals[2], U = a.totals[1];
     // consecutive tiles share a table row: keep them on one XCD (workgroups go round-robin over
     // 8), each XCD taking an equal run of the workgroups that have tiles at all
-    const int per_xcd = ((NT + kWaves - 1) / kWaves + 7) >> 3;
+    const int per_xcd = ((NT + kW - 1) / kW + 7) >> 3;
     if ((int)(blockIdx.x >> 3) >= per_xcd) return;
     const int bid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int t = bid * kWaves + wave;
+    const int t = bid * kW + wave;
+    if (kLdsK) {
+        for (int p = threadIdx.x; p < a.m_pad; p += kW * kWave) lds_posK[p] = a.posK[p];
+        __syncthreads();
+    }
     if (t >= NT) return;
 
     // row of this tile: the last u with tile_off[u] <= t, by a 64-way search
@@ -625,7 +674,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
 
     RowView rv;
     rv.E = a.memo + (size_t)u * a.m_pad;
-    rv.posK = a.posK;
+    rv.posK = kLdsK ? lds_posK : a.posK;
     rv.order = a.order;
     rv.Lf = (float)a.row_len[u];
     rv.nblk = a.m_pad / kWave;
@@ -637,51 +686,25 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) 
         minT[j] = __builtin_inff();
     }
 
-    // ---- main pass: two blocks of 64 positions per step, operands of the next step in flight
-    // (two register sets taking turns, so that nothing is copied)
-    {
-        struct Step { float Ea, Eb; float2 Ka, Kb; };
-        auto fetch = [&](Step& st, int b) {
-            st.Ea = rv.E[b * kWave + lane]; st.Eb = rv.E[(b + 1) * kWave + lane];
-            st.Ka = rv.posK[b * kWave + lane]; st.Kb = rv.posK[(b + 1) * kWave + lane];
-        };
-        auto fold = [&](const Step& st) {
-            const float ka = kappa_of(st.Ka, rv.Lf), kb = kappa_of(st.Kb, rv.Lf);
-#pragma unroll
-            for (int j = 0; j < kTileReq; ++j) {
-                const float Ta = fmaf(c0[j], ka, st.Ea), Tb = fmaf(c0[j], kb, st.Eb);
-                minT[j] = fminf(fminf(minT[j], Ta), Tb);
-            }
-        };
-        // the prefetch is unconditional (past the end it re-reads the last step), so that the
-        // compiler can count exactly how many loads may stay in flight at each use
-        Step s0, s1;
-        const int last = rv.nblk - 2;
-        fetch(s0, 0);
-        for (int b = 0; b < rv.nblk; b += 4) {
-            fetch(s1, min(b + 2, last));
-            __builtin_amdgcn_sched_barrier(0);       // keep the loads ahead of the arithmetic
-            fold(s0);
-            __builtin_amdgcn_sched_barrier(0);
-            fetch(s0, min(b + 4, last));
-            __builtin_amdgcn_sched_barrier(0);
-            if (b + 2 < rv.nblk) fold(s1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
+    // ---- main pass over the requests the tile really has, in eights (most lengths of a batch
+    // have only a few requests, and a tile is one length's)
+    if (nreq <= 8) main_pass<8>(rv, c0, minT, lane);
+    else if (nreq <= 16) main_pass<16>(rv, c0, minT, lane);
+    else if (nreq <= 24) main_pass<24>(rv, c0, minT, lane);
+    else main_pass<32>(rv, c0, minT, lane);
 
     // ---- per request: the least latency and the lane that holds it (lane j keeps request j's)
     float Tm = __builtin_inff();
     int win = kWave;                 // lane holding the minimum; kWave when several do
     static_assert(kTileReq == 32, "eight groups of four requests");
     tile_minima4<0>(minT, Tm, win);
-    tile_minima4<4>(minT, Tm, win);
-    tile_minima4<8>(minT, Tm, win);
-    tile_minima4<12>(minT, Tm, win);
-    tile_minima4<16>(minT, Tm, win);
-    tile_minima4<20>(minT, Tm, win);
-    tile_minima4<24>(minT, Tm, win);
-    tile_minima4<28>(minT, Tm, win);
+    if (nreq > 4) tile_minima4<4>(minT, Tm, win);
+    if (nreq > 8) tile_minima4<8>(minT, Tm, win);
+    if (nreq > 12) tile_minima4<12>(minT, Tm, win);
+    if (nreq > 16) tile_minima4<16>(minT, Tm, win);
+    if (nreq > 20) tile_minima4<20>(minT, Tm, win);
+    if (nreq > 24) tile_minima4<24>(minT, Tm, win);
+    if (nreq > 28) tile_minima4<28>(minT, Tm, win);
 
     // ---- requests with a feasible instance: the first one in capability order
     int foundP = -1;
@@ -911,11 +934,20 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         t.out_inst = out.inst; t.out_slack = out.slack; t.out_fallback = out.fallback; t.out_T = out.T;
         t.n_inst = f->n_inst; t.m_pad = f->m_pad;
         const int64_t max_tiles = (n + kTileReq - 1) / kTileReq + max_rows;
-        unsigned blocks = (unsigned)((max_tiles + kWaves - 1) / kWaves);
+        // 32 waves per compute unit at 8 per SIMD: the coefficient pairs go to LDS when the
+        // 32 / kW workgroups resident together have room for a copy each
+        const size_t k_bytes = (size_t)f->m_pad * sizeof(float2);
+        const int kw = k_bytes <= 32768 ? 8 : k_bytes <= 65536 ? 16 : 4;
+        unsigned blocks = (unsigned)((max_tiles + kw - 1) / kw);
         blocks = (blocks + 7u) & ~7u;
         ProfScope ps(f, kTileRoute + off, s);
-        if (out.T) hipLaunchKernelGGL(k_tile<true>, dim3(blocks), dim3(kBlock), 0, s, t);
-        else hipLaunchKernelGGL(k_tile<false>, dim3(blocks), dim3(kBlock), 0, s, t);
+#define GR_LAUNCH_TILE(W, L) \
+        if (out.T) hipLaunchKernelGGL((k_tile<true, W>), dim3(blocks), dim3(W * kWave), L, s, t); \
+        else hipLaunchKernelGGL((k_tile<false, W>), dim3(blocks), dim3(W * kWave), L, s, t)
+        if (kw == 8) { GR_LAUNCH_TILE(8, k_bytes); }
+        else if (kw == 16) { GR_LAUNCH_TILE(16, k_bytes); }
+        else { GR_LAUNCH_TILE(4, 0); }
+#undef GR_LAUNCH_TILE
     }
     return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
 }
