@@ -210,4 +210,19 @@ __device__ inline T wave_incl_scan(T v)
     return v;
 }
 
+// Inclusive prefix sum of a 32-bit value over the wave without going through
+// LDS: inside each row of 16 lanes by shifts of 1, 2, 4, 8 (a lane without a
+// source adds 0), then lane 15 of rows 0 and 2 onto rows 1 and 3, then lane 31
+// onto rows 2 and 3.
+__device__ inline int wave_incl_scan_i32(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
+    return v;
+}
+
 }  // namespace gr

@@ -62,33 +62,18 @@ __global__ __launch_bounds__(kGroupBlock) void k_hist(ReqSrc s, int* __restrict_
 }
 
 constexpr int kScanBlock = 1024;
+constexpr int kScanWaves = kScanBlock / kWave;
+constexpr int kScanChunks = 32;     // blocks of 64 lengths per wave
+static_assert(kMaxLen + 1 <= kWave * kScanChunks * kScanWaves, "every length has a lane of some wave");
 
-// Inclusive scan over the workgroup; `ws` holds one slot per wave.
-__device__ inline unsigned long long block_incl_scan(unsigned long long v, unsigned long long* ws,
-                                                     unsigned long long& total)
-{
-    const int lane = lane_id(), wave = threadIdx.x / kWave;
-    v = wave_incl_scan(v);
-    __syncthreads();
-    if (lane == kWave - 1) ws[wave] = v;
-    __syncthreads();
-    unsigned long long before = 0;
-    total = 0;
-#pragma unroll
-    for (int w = 0; w < kScanBlock / kWave; ++w) {
-        const unsigned long long x = ws[w];
-        if (w < wave) before += x;
-        total += x;
-    }
-    return v + before;
-}
-
-// One workgroup walks the length histogram (copied to LDS; a thread owns a run
-// of consecutive lengths): the first slot of each length in grouped order, the
-// list of lengths present ("rows") and the row of each such length, the first
-// tile of each row (a tile = up to kTileReq requests of one length), and the
-// totals.  The histogram is cleared
-// for the next call.
+// One workgroup walks the length histogram: the first slot of each length in
+// grouped order, the list of lengths present ("rows") and the row of each such
+// length, the first tile of each row (a tile = up to kTileReq requests of one
+// length), and the totals.  A wave owns a run of consecutive blocks of 64
+// lengths (lane = length within the block, so every access is a row of
+// consecutive addresses); it keeps its counts in registers, adds them up, takes
+// the sum of the waves before it from LDS, and then scans block by block.  The
+// histogram is cleared for the next call.
 __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, int* __restrict__ len_base,
                                                      int* __restrict__ row_len, int* __restrict__ row_off,
                                                      int* __restrict__ tile_off, int* __restrict__ len_row,
@@ -96,39 +81,74 @@ __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, 
                                                      int* __restrict__ out_n, int bins)
 {
     extern __shared__ uint32_t lds[];
-    int* cnt = reinterpret_cast<int*>(lds);
-    __shared__ unsigned long long ws[kScanBlock / kWave];
-    const int tid = threadIdx.x;
-    for (int i = tid; i < bins; i += kScanBlock) { cnt[i] = len_cnt[i]; len_cnt[i] = 0; }
-    __syncthreads();
-    const int per = ((bins + kScanBlock - 1) / kScanBlock) | 1;   // odd: no LDS bank conflicts
-    const int i0 = min(tid * per, bins), i1 = min(i0 + per, bins);
-    unsigned long long mine = 0, rows = 0;     // requests in the low half, tiles in the high half
-    for (int i = i0; i < i1; ++i) {
-        const unsigned c = (unsigned)cnt[i];
-        mine += (unsigned long long)c | ((unsigned long long)((c + kTileReq - 1) / kTileReq) << 32);
-        rows += c > 0;
-    }
-    unsigned long long tot1, tot2;
-    unsigned long long run = block_incl_scan(mine, ws, tot1) - mine;
-    int u = (int)(block_incl_scan(rows, ws, tot2) - rows);
-    for (int i = i0; i < i1; ++i) {
-        const unsigned c = (unsigned)cnt[i];
-        cnt[i] = (int)(run & 0xFFFFFFFFull);
-        len_ceil[i] = u;          // rows shorter than i = the first row that is at least i long
-        if (c) {
-            len_row[i] = u;
-            row_len[u] = i;
-            row_off[u] = (int)(run & 0xFFFFFFFFull);
-            tile_off[u] = (int)(run >> 32);
-            ++u;
+    unsigned* held = lds;                                // the counts, for the second pass
+    __shared__ unsigned long long w_sum[kScanWaves];     // requests in the low half, tiles in the high half
+    __shared__ int w_rows[kScanWaves];
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const int chunks = (bins + kWave - 1) / kWave;
+    const int per = (chunks + kScanWaves - 1) / kScanWaves;     // <= kScanChunks, checked by the host
+    const int c0 = wave * per;
+    const auto packed = [](unsigned c) {
+        return (unsigned long long)c | ((unsigned long long)((c + kTileReq - 1) / kTileReq) << 32);
+    };
+
+    unsigned long long mine = 0;
+    int rows = 0;
+    {
+        unsigned cnt[kScanChunks];
+#pragma unroll
+        for (int k = 0; k < kScanChunks; ++k) {     // all loads first, then their uses
+            const int i = (c0 + k) * kWave + lane;
+            cnt[k] = k < per && i < bins ? (unsigned)len_cnt[i] : 0u;
         }
-        run += (unsigned long long)c | ((unsigned long long)((c + kTileReq - 1) / kTileReq) << 32);
+#pragma unroll
+        for (int k = 0; k < kScanChunks; ++k) {
+            const int i = (c0 + k) * kWave + lane;
+            if (k < per && i < bins) { held[i] = cnt[k]; len_cnt[i] = 0; }
+            mine += packed(cnt[k]);
+            rows += cnt[k] > 0;
+        }
     }
+    mine = wave_sum(mine);
+    rows = wave_sum(rows);
+    if (lane == 0) { w_sum[wave] = mine; w_rows[wave] = rows; }
     __syncthreads();
-    for (int i = tid; i < bins; i += kScanBlock) len_base[i] = cnt[i];
-    if (tid == 0) {
-        const int n = (int)(tot1 & 0xFFFFFFFFull), U = (int)tot2, NT = (int)(tot1 >> 32);
+    unsigned long long run = 0, total = 0;
+    int u = 0, U = 0;
+#pragma unroll
+    for (int w = 0; w < kScanWaves; ++w) {
+        const unsigned long long x = w_sum[w];
+        const int r = w_rows[w];
+        if (w < wave) { run += x; u += r; }
+        total += x;
+        U += r;
+    }
+
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int at_req = (int)(run & 0xFFFFFFFFull), at_tile = (int)(run >> 32);
+    for (int k = 0; k < per; ++k) {
+        const int i = (c0 + k) * kWave + lane;
+        const int c = i < bins ? (int)held[i] : 0;     // written by this same lane above
+        const int tiles = (c + kTileReq - 1) / kTileReq;
+        const int req_incl = wave_incl_scan_i32(c), tile_incl = wave_incl_scan_i32(tiles);
+        const unsigned long long present = __ballot(c > 0);
+        const int row = u + __popcll(present & below);
+        if (i < bins) {
+            len_base[i] = at_req + req_incl - c;
+            len_ceil[i] = row;          // rows shorter than i = the first row that is at least i long
+            if (c) {
+                len_row[i] = row;
+                row_len[row] = i;
+                row_off[row] = at_req + req_incl - c;
+                tile_off[row] = at_tile + tile_incl - tiles;
+            }
+        }
+        at_req += __builtin_amdgcn_readlane(req_incl, kWave - 1);
+        at_tile += __builtin_amdgcn_readlane(tile_incl, kWave - 1);
+        u += __popcll(present);
+    }
+    if (threadIdx.x == 0) {
+        const int n = (int)(total & 0xFFFFFFFFull), NT = (int)(total >> 32);
         row_off[U] = n;
         tile_off[U] = NT;
         totals[0] = n; totals[1] = U; totals[2] = NT;
