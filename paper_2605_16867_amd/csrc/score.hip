@@ -428,6 +428,119 @@ __device__ inline void tile_minima4(const float (&minT)[kTileReq], float& Tm, in
     writelane<kJ0 + 3>(win, winner(__ballot(minT[kJ0 + 3] == m3)));
 }
 
+// All 32 wave-wide minima of a full tile at once (no NaNs among the inputs).
+// Five halving steps: the lanes of a pair (lane numbers differing in bit s)
+// split the requests they still hold by bit s of the request number, each
+// passing the other the half it gives up and keeping the minimum of the half
+// it holds; then the two halves of the wave are combined.  On return lane l
+// holds the minimum of request l mod 32 over the 64 lanes: 31 + 1 minima
+// instead of 32 * 6.
+//
+// A step's minima are single instructions that read the partner's register
+// through DPP, written out here because the compiler would pair every such
+// read with a separate move and a canonicalising maximum.  No instruction of a
+// group reads what another of the group wrote; the leading s_nop keeps the
+// distance the hardware asks for between the instructions that produced the
+// inputs and the first DPP read.
+__device__ inline float tile_minima_all(const float (&m)[kTileReq], int lane)
+{
+    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4, b3 = lane & 8, b4 = lane & 16;
+    float r1[16], r2[8], r3[4], r4[2];
+    // eight minima: outputs %0-%7, what each lane sends %8-%15, what it keeps %16-%23
+#define GR_MIN8(o, sd, kp, ctrl)                                                                                     \
+    asm volatile("s_nop 1\n\t"                                                                                       \
+                 "v_min_f32_dpp %0, %8, %16 " ctrl "\n\t"                                                            \
+                 "v_min_f32_dpp %1, %9, %17 " ctrl "\n\t"                                                            \
+                 "v_min_f32_dpp %2, %10, %18 " ctrl "\n\t"                                                           \
+                 "v_min_f32_dpp %3, %11, %19 " ctrl "\n\t"                                                           \
+                 "v_min_f32_dpp %4, %12, %20 " ctrl "\n\t"                                                           \
+                 "v_min_f32_dpp %5, %13, %21 " ctrl "\n\t"                                                           \
+                 "v_min_f32_dpp %6, %14, %22 " ctrl "\n\t"                                                           \
+                 "v_min_f32_dpp %7, %15, %23 " ctrl                                                                  \
+                 : "=&v"(o[0]), "=&v"(o[1]), "=&v"(o[2]), "=&v"(o[3]), "=&v"(o[4]), "=&v"(o[5]), "=&v"(o[6]),        \
+                   "=&v"(o[7])                                                                                       \
+                 : "v"(sd[0]), "v"(sd[1]), "v"(sd[2]), "v"(sd[3]), "v"(sd[4]), "v"(sd[5]), "v"(sd[6]), "v"(sd[7]),   \
+                   "v"(kp[0]), "v"(kp[1]), "v"(kp[2]), "v"(kp[3]), "v"(kp[4]), "v"(kp[5]), "v"(kp[6]), "v"(kp[7]))
+    {   // lane ^ 1
+        float keep[16], send[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            keep[k] = b0 ? m[2 * k + 1] : m[2 * k];
+            send[k] = b0 ? m[2 * k] : m[2 * k + 1];
+        }
+        float *o = r1, *sd = send, *kp = keep;
+        GR_MIN8(o, sd, kp, "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf");
+        o += 8; sd += 8; kp += 8;
+        GR_MIN8(o, sd, kp, "quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf");
+    }
+    {   // lane ^ 2
+        float keep[8], send[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            keep[k] = b1 ? r1[2 * k + 1] : r1[2 * k];
+            send[k] = b1 ? r1[2 * k] : r1[2 * k + 1];
+        }
+        GR_MIN8(r2, send, keep, "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf");
+    }
+#undef GR_MIN8
+    {   // lane ^ 4: lanes 0-3 and 8-11 of a row of 16 read four lanes up, the others four lanes down
+        float keep[4], send[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            keep[k] = b2 ? r2[2 * k + 1] : r2[2 * k];
+            send[k] = b2 ? r2[2 * k] : r2[2 * k + 1];
+        }
+        asm volatile("s_nop 1\n\t"
+                     "v_min_f32_dpp %0, %4, %8 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
+                     "v_min_f32_dpp %1, %5, %9 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
+                     "v_min_f32_dpp %2, %6, %10 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
+                     "v_min_f32_dpp %3, %7, %11 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
+                     "v_min_f32_dpp %0, %4, %8 row_shr:4 row_mask:0xf bank_mask:0xa\n\t"
+                     "v_min_f32_dpp %1, %5, %9 row_shr:4 row_mask:0xf bank_mask:0xa\n\t"
+                     "v_min_f32_dpp %2, %6, %10 row_shr:4 row_mask:0xf bank_mask:0xa\n\t"
+                     "v_min_f32_dpp %3, %7, %11 row_shr:4 row_mask:0xf bank_mask:0xa"
+                     : "=&v"(r3[0]), "=&v"(r3[1]), "=&v"(r3[2]), "=&v"(r3[3])
+                     : "v"(send[0]), "v"(send[1]), "v"(send[2]), "v"(send[3]),
+                       "v"(keep[0]), "v"(keep[1]), "v"(keep[2]), "v"(keep[3]));
+    }
+    {   // lane ^ 8: a rotation of the row of 16 by 8
+        float keep[2], send[2];
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            keep[k] = b3 ? r3[2 * k + 1] : r3[2 * k];
+            send[k] = b3 ? r3[2 * k] : r3[2 * k + 1];
+        }
+        asm volatile("s_nop 1\n\t"
+                     "v_min_f32_dpp %0, %2, %4 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+                     "v_min_f32_dpp %1, %3, %5 row_ror:8 row_mask:0xf bank_mask:0xf"
+                     : "=&v"(r4[0]), "=&v"(r4[1])
+                     : "v"(send[0]), "v"(send[1]), "v"(keep[0]), "v"(keep[1]));
+    }
+    const float keep = b4 ? r4[1] : r4[0], send = b4 ? r4[0] : r4[1];
+    // lane ^ 16 by a swizzle in bit mode (and 0x1f, or 0, xor 0x10), lane ^ 32 by a permute; both
+    // values come back as they were stored, so the minima below need no canonicalising
+    float r = __builtin_fminf(keep, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(send), 0x401F)));
+    return __builtin_fminf(r, __shfl_xor(r, 32, kWave));
+}
+
+// The lane that holds request kJ's minimum `Tm` (lane kJ of it), kWave when
+// several do, into lane kJ of `win`.
+template <int kJ>
+__device__ inline void tile_winner(const float (&minT)[kTileReq], float Tm, int& win)
+{
+    const unsigned long long cand = __ballot(minT[kJ] == readlane_f(Tm, kJ));
+    writelane<kJ>(win, (cand && !(cand & (cand - 1))) ? __ffsll((long long)cand) - 1 : kWave);
+}
+
+template <int kJ, int kEnd>
+__device__ inline void tile_winners(const float (&minT)[kTileReq], float Tm, int& win)
+{
+    if constexpr (kJ < kEnd) {
+        tile_winner<kJ>(minT, Tm, win);
+        tile_winners<kJ + 1, kEnd>(minT, Tm, win);
+    }
+}
+
 struct RowView {
     const float* __restrict__ E;       // this length's row of the memo table
     const float2* __restrict__ posK;
@@ -601,9 +714,13 @@ __device__ __forceinline__ void main_pass(const RowView& rv, const float (&c0)[k
                                           int lane)
 {
     struct Step { float Ea, Eb; float2 Ka, Kb; };
+    // block starts are wave-uniform (scalar address arithmetic), the lane adds a fixed offset
+    const unsigned ul = (unsigned)lane;
     auto fetch = [&](Step& st, int b) {
-        st.Ea = rv.E[b * kWave + lane]; st.Eb = rv.E[(b + 1) * kWave + lane];
-        st.Ka = rv.posK[b * kWave + lane]; st.Kb = rv.posK[(b + 1) * kWave + lane];
+        const float* __restrict__ eb = rv.E + (unsigned)b * kWave;
+        const float2* __restrict__ kb = rv.posK + (unsigned)b * kWave;
+        st.Ea = eb[ul]; st.Eb = eb[kWave + ul];
+        st.Ka = kb[ul]; st.Kb = kb[kWave + ul];
     };
     auto fold = [&](const Step& st) {
         const float ka = kappa_of(st.Ka, rv.Lf), kb = kappa_of(st.Kb, rv.Lf);
@@ -717,14 +834,15 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(8, 8
     float Tm = __builtin_inff();
     int win = kWave;                 // lane holding the minimum; kWave when several do
     static_assert(kTileReq == 32, "eight groups of four requests");
-    tile_minima4<0>(minT, Tm, win);
-    if (nreq > 4) tile_minima4<4>(minT, Tm, win);
-    if (nreq > 8) tile_minima4<8>(minT, Tm, win);
-    if (nreq > 12) tile_minima4<12>(minT, Tm, win);
-    if (nreq > 16) tile_minima4<16>(minT, Tm, win);
-    if (nreq > 20) tile_minima4<20>(minT, Tm, win);
-    if (nreq > 24) tile_minima4<24>(minT, Tm, win);
-    if (nreq > 28) tile_minima4<28>(minT, Tm, win);
+    if (nreq > 16) {
+        Tm = tile_minima_all(minT, lane);
+        tile_winners<0, kTileReq>(minT, Tm, win);
+    } else {
+        tile_minima4<0>(minT, Tm, win);
+        if (nreq > 4) tile_minima4<4>(minT, Tm, win);
+        if (nreq > 8) tile_minima4<8>(minT, Tm, win);
+        if (nreq > 12) tile_minima4<12>(minT, Tm, win);
+    }
 
     // ---- requests with a feasible instance: the first one in capability order
     int foundP = -1;
