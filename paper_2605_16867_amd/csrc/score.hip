@@ -230,10 +230,10 @@ struct MemoArgs {
 // and a run of consecutive distinct lengths ("rows", ascending), kMemoU at a
 // time.  The segment of a length is k = #{R_i <= L}.  Both the instance's
 // lengths R and the rows are sorted, so k is found by counting instead of
-// searching: the instance's entries that fall between the previous pass's last
-// row and this pass's last row (a handful) each add one to the counter of the
-// first row that is at least as long (a table over all lengths from the
-// grouping pass), and a prefix sum over the pass's counters, carried from pass
+// searching: every entry is first replaced by the first row that is at least
+// as long (a table over all lengths from the grouping pass, looked up once per
+// entry); the entries whose row lies in a pass (a handful) each add one to that
+// row's counter, and a prefix sum over the pass's counters, carried from pass
 // to pass, gives k for every row.  Each pass is turned in LDS, in one of two
 // buffers so that one barrier per pass is enough, and written in runs of kMemoP
 // positions per length.
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
     const int p0 = blockIdx.x * kMemoP;
     const int tid = threadIdx.x, lane = lane_id(), pi = tid / kWave;
     int* cnt = reinterpret_cast<int*>(tiles + 2 * kMemoTile) + pi * kMemoU;
-    uint16_t* sR = reinterpret_cast<uint16_t*>(tiles + 2 * kMemoTile + kMemoP * kMemoU) + (size_t)pi * a.cap;
+    uint16_t* sRow = reinterpret_cast<uint16_t*>(tiles + 2 * kMemoTile + kMemoP * kMemoU) + (size_t)pi * a.cap;
     constexpr int kPerLane = kMemoU / kWave;
     const int p = p0 + pi;
     const int g = p < a.n_inst ? a.order[p] : -1;
@@ -265,20 +265,24 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
         head = a.headGH[g];
         gam = a.keep * (float)a.cls[a.inst_class[g]].gamma;
         GH = a.tabGH + (size_t)g * a.cap;
-        const uint4* srcR = reinterpret_cast<const uint4*>(a.tabR + (size_t)g * a.cap);
-        for (int c = lane; c * 8 < N; c += kWave) reinterpret_cast<uint4*>(sR)[c] = srcR[c];
+        // the row of each of the instance's sorted lengths (how many rows are shorter), looked up
+        // once; from here on the lengths themselves are not needed
+        const uint16_t* __restrict__ srcR = a.tabR + (size_t)g * a.cap;
+#pragma unroll 4
+        for (int e = lane; e < N; e += kWave) sRow[e] = (uint16_t)a.len_ceil[srcR[e]];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    // entries not longer than the row before the run: the one search of this wave (every lane the same)
+    // entries that belong to rows before the run (the rows are ascending with the entries: the
+    // lanes that still find one form a prefix)
     int kb = 0;
     if (g >= 0 && ub > 0 && ub < ue) {
-        const int Lprev = a.row_len[ub - 1];
-        for (int step = a.cap; step >= 1; step >>= 1) {
-            const int probe = kb + step;
-            if (probe <= N && (int)sR[probe - 1] <= Lprev) kb = probe;
+        for (int e = lane;; e += kWave) {
+            const unsigned long long m = __ballot(e < N && (int)sRow[min(e, N - 1)] < ub && N > 0);
+            kb += __popcll(m);
+            if (m != ~0ull) break;
         }
     }
 
@@ -290,11 +294,12 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            const int Lhi = a.row_len[min(u0 + kMemoU, U) - 1];
+            const int hi = min(u0 + kMemoU, U);
             int taken = 0;
-            for (int e = kb + lane;; e += kWave) {       // the lanes that still find an entry form a prefix
-                const bool ok = e < N && (int)sR[min(e, N - 1)] <= Lhi && N > 0;
-                if (ok) atomicAdd(&cnt[a.len_ceil[sR[e]] - u0], 1);
+            for (int e = kb + lane;; e += kWave) {
+                const int row = e < N ? (int)sRow[e] : hi;
+                const bool ok = row < hi;
+                if (ok) atomicAdd(&cnt[row - u0], 1);
                 const unsigned long long m = __ballot(ok);
                 taken += __popcll(m);
                 if (m != ~0ull) break;
@@ -304,7 +309,7 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             int4 c = reinterpret_cast<int4*>(cnt)[lane];      // rows 4 lane .. 4 lane + 3 of the pass
             c.y += c.x; c.z += c.y; c.w += c.z;
-            const int before = kb + wave_incl_scan(c.w) - c.w;
+            const int before = kb + wave_incl_scan_i32(c.w) - c.w;
             c.x += before; c.y += before; c.z += before; c.w += before;
             reinterpret_cast<int4*>(cnt)[lane] = c;           // now k of each row
             kb += taken;
