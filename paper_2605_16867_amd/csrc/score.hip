@@ -767,12 +767,15 @@ constexpr int kSparseFeasible = 8;   // up to this many feasible requests of a t
 // found by recomputing the positions of the lane that holds it (the earliest
 // position in capability order among equal minima).
 //
-// kW waves per workgroup.  With kW > 4 the workgroup first copies the (delta,
-// gamma) pairs of all positions, which every tile reads in full, into LDS:
-// 32 / kW workgroups of m_pad * 8 bytes share a compute unit, and the texture
-// path is left to the table rows and the gathers of the search for the minimum.
+// kW waves per workgroup, six waves per SIMD (80 vector registers: the 32
+// running minima, two sets of operands in flight and the epilogue's
+// temporaries fit without spilling).  With kW > 4 the workgroup first copies
+// the (delta, gamma) pairs of all positions, which every tile reads in full,
+// into LDS: 24 / kW workgroups of m_pad * 8 bytes share a compute unit, and the
+// texture path is left to the table rows and the gathers of the search for the
+// minimum.
 template <bool kWriteT, int kW>
-__global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_tile(TileArgs a)
+__global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6))) void k_tile(TileArgs a)
 {
     constexpr bool kLdsK = kW > 4;
     extern __shared__ float2 lds_posK[];
@@ -1077,10 +1080,10 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         t.out_inst = out.inst; t.out_slack = out.slack; t.out_fallback = out.fallback; t.out_T = out.T;
         t.n_inst = f->n_inst; t.m_pad = f->m_pad;
         const int64_t max_tiles = (n + kTileReq - 1) / kTileReq + max_rows;
-        // 32 waves per compute unit at 8 per SIMD: the coefficient pairs go to LDS when the
-        // 32 / kW workgroups resident together have room for a copy each
+        // 24 waves per compute unit (6 per SIMD): the coefficient pairs go to LDS when the
+        // 24 / kW workgroups resident together have room for a copy each
         const size_t k_bytes = (size_t)f->m_pad * sizeof(float2);
-        const int kw = k_bytes <= 32768 ? 8 : k_bytes <= 65536 ? 16 : 4;
+        const int kw = k_bytes <= 49152 ? 8 : k_bytes <= 65536 ? 12 : 4;
         unsigned blocks = (unsigned)((max_tiles + kw - 1) / kw);
         blocks = (blocks + 7u) & ~7u;
         ProfScope ps(f, kTileRoute + off, s);
@@ -1088,7 +1091,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         if (out.T) hipLaunchKernelGGL((k_tile<true, W>), dim3(blocks), dim3(W * kWave), L, s, t); \
         else hipLaunchKernelGGL((k_tile<false, W>), dim3(blocks), dim3(W * kWave), L, s, t)
         if (kw == 8) { GR_LAUNCH_TILE(8, k_bytes); }
-        else if (kw == 16) { GR_LAUNCH_TILE(16, k_bytes); }
+        else if (kw == 12) { GR_LAUNCH_TILE(12, k_bytes); }
         else { GR_LAUNCH_TILE(4, 0); }
 #undef GR_LAUNCH_TILE
     }
