@@ -52,6 +52,8 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--latency-iters", type=int, default=100,
+                    help="calls of gr_score_route timed one by one for the route-batch latency")
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="heavy", help="tiny | mid | large | migrate | heavy")
     ap.add_argument("--prefixes", type=float, default=0.0,
@@ -188,6 +190,19 @@ def main():
         if not prof.get(name, (0.0, 0))[1]:
             prof[name] = v
 
+    # route-batch latency: gr_score_route alone on the warm handle, host clock around call + sync
+    route_ms = []
+    if R:
+        h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"],
+                          d["q_off"], d["q_prompt"], d["q_len"], fin)
+        for _ in range(a.latency_iters + 5):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, slack)
+            torch.cuda.synchronize()
+            route_ms.append((time.perf_counter() - t) * 1e3)
+        route_ms = sorted(route_ms[5:])
+
     # a plain device-to-device copy of known size, outside the timed region: the
     # reference against which hardware memory counters of a profiled run are scaled
     cal_src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
@@ -240,6 +255,16 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if route_ms:
+        out["route_batch_latency_ms"] = {
+            "requests": R, "iters": len(route_ms), "median": route_ms[len(route_ms) // 2],
+            "p99": route_ms[min(len(route_ms) - 1, int(0.99 * len(route_ms)))]}
+    # achieved HBM rate as a share of the 8 TB/s peak: the streaming kernel on its algorithmic
+    # bytes, the dominant kernel on the bytes the hardware counters saw
+    out["hbm_pct_of_peak"] = {"k_build (algorithmic bytes)": 100.0 * kernels["k_build"]["frac"]}
+    if traffic is not None:
+        out["hbm_pct_of_peak"][dominant + " (counter bytes)"] = (
+            100.0 * traffic / (dk["avg_ms"] * 1e-3) / (HBM_PEAK_GBS * 1e9))
     if a.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(fl, pairs_route, pairs_mig, entries, n_flagged, a.cpu_seconds)
     h.close()
