@@ -127,6 +127,38 @@ def test_one_length_many_requests_and_all_lengths_distinct():
     parity.run_and_check(fl)
 
 
+def test_every_tile_filling():
+    """Lengths with 1 .. 70 requests each: tiles of every filling (the main pass
+    runs over the requests a tile has, in eights; small tiles and full tiles
+    take their minima differently), with deadlines on both sides of feasible."""
+    rng = np.random.default_rng(11)
+    acts = [rand_entries(rng, int(n)) for n in rng.integers(0, 120, 200)]
+    cls = rng.integers(0, 3, 200)
+    counts = [1, 2, 3, 4, 5, 7, 8, 9, 12, 13, 15, 16, 17, 20, 23, 24, 25, 28, 31, 32, 33, 40, 48, 63, 64, 65, 70]
+    lens = np.repeat(rng.permutation(3000)[:len(counts)] + 1, counts)
+    inc = np.stack([rng.integers(128, 2049, len(lens)), lens], 1)
+    for scale in (0.5, 3.0, 30.0):
+        fl = fleet(cls, acts, [[]] * 200, inc, rng.uniform(0.5, 2, len(lens)) * scale * solo(inc[:, 0], inc[:, 1]))
+        sim = oracle.simulate(fl)
+        fl.act_budget = (sim.act_finish * rng.uniform(0.5, 1.5, len(sim.act_finish))).astype(np.float32)
+        parity.run_and_check(fl)
+
+
+@pytest.mark.parametrize("n_inst", [6208, 8320])
+def test_wide_fleets(n_inst):
+    """More instances than the scoring kernel's small-workgroup variant keeps
+    coefficient pairs for in LDS (larger workgroups, then global memory)."""
+    rng = np.random.default_rng(n_inst)
+    acts = [rand_entries(rng, int(n)) for n in rng.integers(0, 7, n_inst)]
+    cls = rng.integers(0, 3, n_inst)
+    inc = np.stack([rng.integers(128, 2049, 300), rng.choice([3, 50, 51, 400, 2000], 300)], 1)
+    fl = fleet(cls, acts, [[]] * n_inst, inc, rng.uniform(0.8, 3, 300) * solo(inc[:, 0], inc[:, 1]))
+    sim = oracle.simulate(fl)
+    fl.act_budget = (sim.act_finish * rng.uniform(0.5, 1.5, len(sim.act_finish))).astype(np.float32)
+    rep = parity.run_and_check(fl)
+    assert rep["finish_rel_err"] < 1e-6
+
+
 def test_special_budgets():
     rng = np.random.default_rng(4)
     acts = [rand_entries(rng, 200) for _ in range(9)]
