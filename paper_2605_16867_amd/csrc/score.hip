@@ -63,77 +63,76 @@ __global__ __launch_bounds__(kGroupBlock) void k_hist(ReqSrc s, int* __restrict_
 
 constexpr int kScanBlock = 1024;
 constexpr int kScanWaves = kScanBlock / kWave;
-constexpr int kScanChunks = 32;     // blocks of 64 lengths per wave
-static_assert(kMaxLen + 1 <= kWave * kScanChunks * kScanWaves, "every length has a lane of some wave");
+constexpr int kScanGroups = 16;     // workgroups
+constexpr int kScanChunks = 2;      // blocks of 64 lengths per wave
+static_assert(kMaxLen + 1 <= kWave * kScanChunks * kScanWaves * kScanGroups, "every length has a lane of some wave");
 
-// One workgroup walks the length histogram: the first slot of each length in
+// Prefix sums over the length histogram: the first slot of each length in
 // grouped order, the list of lengths present ("rows") and the row of each such
 // length, the first tile of each row (a tile = up to kTileReq requests of one
-// length), and the totals.  A wave owns a run of consecutive blocks of 64
+// length), and the totals.  A wave owns one or two blocks of 64 consecutive
 // lengths (lane = length within the block, so every access is a row of
-// consecutive addresses); it keeps its counts in registers, adds them up, takes
-// the sum of the waves before it from LDS, and then scans block by block.  The
-// histogram is cleared for the next call.
-__global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, int* __restrict__ len_base,
+// consecutive addresses).  The histogram is small and sits in L2, so instead
+// of passing sums from workgroup to workgroup each workgroup adds up
+// everything before its own lengths itself; the last one also has the totals.
+// The histogram is left as it is (the scatter clears it for the next call).
+__global__ __launch_bounds__(kScanBlock) void k_scan(const int* __restrict__ len_cnt, int* __restrict__ len_base,
                                                      int* __restrict__ row_len, int* __restrict__ row_off,
                                                      int* __restrict__ tile_off, int* __restrict__ len_row,
                                                      int* __restrict__ len_ceil, int* __restrict__ totals,
                                                      int* __restrict__ out_n, int bins)
 {
-    extern __shared__ uint32_t lds[];
-    unsigned* held = lds;                                // the counts, for the second pass
-    __shared__ unsigned long long w_sum[kScanWaves];     // requests in the low half, tiles in the high half
-    __shared__ int w_rows[kScanWaves];
+    __shared__ int w_req[2][kScanWaves], w_tile[2][kScanWaves], w_rows[2][kScanWaves];
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int chunks = (bins + kWave - 1) / kWave;
-    const int per = (chunks + kScanWaves - 1) / kScanWaves;     // <= kScanChunks, checked by the host
-    const int c0 = wave * per;
-    const auto packed = [](unsigned c) {
-        return (unsigned long long)c | ((unsigned long long)((c + kTileReq - 1) / kTileReq) << 32);
-    };
+    const int per = (chunks + kScanWaves * kScanGroups - 1) / (kScanWaves * kScanGroups);    // 1 or 2
+    const int first = min((int)blockIdx.x * kScanWaves * per * kWave, bins);    // first length of this workgroup
+    const auto tiles_of = [](int c) { return (c + kTileReq - 1) / kTileReq; };
+    const auto wave_total = [](int v) { return __builtin_amdgcn_readlane(wave_incl_scan_i32(v), kWave - 1); };
 
-    unsigned long long mine = 0;
-    int rows = 0;
-    {
-        unsigned cnt[kScanChunks];
-#pragma unroll
-        for (int k = 0; k < kScanChunks; ++k) {     // all loads first, then their uses
-            const int i = (c0 + k) * kWave + lane;
-            cnt[k] = k < per && i < bins ? (unsigned)len_cnt[i] : 0u;
-        }
-#pragma unroll
-        for (int k = 0; k < kScanChunks; ++k) {
-            const int i = (c0 + k) * kWave + lane;
-            if (k < per && i < bins) { held[i] = cnt[k]; len_cnt[i] = 0; }
-            mine += packed(cnt[k]);
-            rows += cnt[k] > 0;
-        }
+    // everything before this workgroup's lengths, a slice per thread
+    int b_req = 0, b_tile = 0, b_rows = 0;
+#pragma unroll 8
+    for (int i = threadIdx.x; i < first; i += kScanBlock) {
+        const int c = len_cnt[i];
+        b_req += c; b_tile += tiles_of(c); b_rows += c > 0;
     }
-    mine = wave_sum(mine);
-    rows = wave_sum(rows);
-    if (lane == 0) { w_sum[wave] = mine; w_rows[wave] = rows; }
+    // this wave's own lengths
+    int cnt[kScanChunks], m_req = 0, m_tile = 0, m_rows = 0;
+#pragma unroll
+    for (int k = 0; k < kScanChunks; ++k) {
+        const int i = first + (wave * per + k) * kWave + lane;
+        cnt[k] = k < per && i < bins ? len_cnt[i] : 0;
+        m_req += cnt[k]; m_tile += tiles_of(cnt[k]); m_rows += cnt[k] > 0;
+    }
+    b_req = wave_total(b_req); b_tile = wave_total(b_tile); b_rows = wave_total(b_rows);
+    m_req = wave_total(m_req); m_tile = wave_total(m_tile); m_rows = wave_total(m_rows);
+    if (lane == 0) {
+        w_req[0][wave] = b_req; w_tile[0][wave] = b_tile; w_rows[0][wave] = b_rows;
+        w_req[1][wave] = m_req; w_tile[1][wave] = m_tile; w_rows[1][wave] = m_rows;
+    }
     __syncthreads();
-    unsigned long long run = 0, total = 0;
-    int u = 0, U = 0;
+    int at_req = 0, at_tile = 0, u = 0, all_req = 0, all_tile = 0, all_rows = 0;
 #pragma unroll
     for (int w = 0; w < kScanWaves; ++w) {
-        const unsigned long long x = w_sum[w];
-        const int r = w_rows[w];
-        if (w < wave) { run += x; u += r; }
-        total += x;
-        U += r;
+        const int before_r = w_req[0][w], before_t = w_tile[0][w], before_u = w_rows[0][w];
+        const int own_r = w_req[1][w], own_t = w_tile[1][w], own_u = w_rows[1][w];
+        at_req += before_r + (w < wave ? own_r : 0);
+        at_tile += before_t + (w < wave ? own_t : 0);
+        u += before_u + (w < wave ? own_u : 0);
+        all_req += before_r + own_r; all_tile += before_t + own_t; all_rows += before_u + own_u;
     }
 
     const unsigned long long below = (1ull << lane) - 1ull;
-    int at_req = (int)(run & 0xFFFFFFFFull), at_tile = (int)(run >> 32);
-    for (int k = 0; k < per; ++k) {
-        const int i = (c0 + k) * kWave + lane;
-        const int c = i < bins ? (int)held[i] : 0;     // written by this same lane above
-        const int tiles = (c + kTileReq - 1) / kTileReq;
+#pragma unroll
+    for (int k = 0; k < kScanChunks; ++k) {
+        const int i = first + (wave * per + k) * kWave + lane;
+        const int c = cnt[k];
+        const int tiles = tiles_of(c);
         const int req_incl = wave_incl_scan_i32(c), tile_incl = wave_incl_scan_i32(tiles);
         const unsigned long long present = __ballot(c > 0);
         const int row = u + __popcll(present & below);
-        if (i < bins) {
+        if (k < per && i < bins) {
             len_base[i] = at_req + req_incl - c;
             len_ceil[i] = row;          // rows shorter than i = the first row that is at least i long
             if (c) {
@@ -147,19 +146,18 @@ __global__ __launch_bounds__(kScanBlock) void k_scan(int* __restrict__ len_cnt, 
         at_tile += __builtin_amdgcn_readlane(tile_incl, kWave - 1);
         u += __popcll(present);
     }
-    if (threadIdx.x == 0) {
-        const int n = (int)(total & 0xFFFFFFFFull), NT = (int)(total >> 32);
-        row_off[U] = n;
-        tile_off[U] = NT;
-        totals[0] = n; totals[1] = U; totals[2] = NT;
-        if (out_n) *out_n = n;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {      // the last workgroup has seen every length
+        row_off[all_rows] = all_req;
+        tile_off[all_rows] = all_tile;
+        totals[0] = all_req; totals[1] = all_rows; totals[2] = all_tile;
+        if (out_n) *out_n = all_req;
     }
 }
 
 // Requests into grouped order.  Per workgroup: count per length in LDS, reserve
 // that many slots of each length with one global atomic, hand the slots out.
 template <bool kMigrate, int kItems>
-__global__ __launch_bounds__(kGroupBlock) void k_scatter(ReqSrc s, int* __restrict__ len_base,
+__global__ __launch_bounds__(kGroupBlock) void k_scatter(ReqSrc s, int* __restrict__ len_cnt, int* __restrict__ len_base,
                                                     const int* __restrict__ rank, ReqRec* __restrict__ recs,
                                                     int* __restrict__ out_inst, float* __restrict__ out_slack,
                                                     int bins, int max_len, int n_inst)
@@ -168,6 +166,8 @@ __global__ __launch_bounds__(kGroupBlock) void k_scatter(ReqSrc s, int* __restri
     int* slot = reinterpret_cast<int*>(lds);
     const int tid = threadIdx.x;
     for (int L = tid; L < bins; L += kGroupBlock) slot[L] = 0;
+    // the histogram has been turned into slot bases: clear it for the next call
+    for (int L = blockIdx.x * kGroupBlock + tid; L < bins; L += gridDim.x * kGroupBlock) len_cnt[L] = 0;
     __syncthreads();
     const int64_t base = (int64_t)blockIdx.x * (kGroupBlock * kItems);
     int Ls[kItems];
@@ -1017,7 +1017,7 @@ int score_prepare(gr_fleet* f)
     const bool ok = set_lds(k_hist<false, 4>, hist) && set_lds(k_hist<true, 4>, hist) &&
                     set_lds(k_hist<false, 16>, hist) && set_lds(k_hist<true, 16>, hist) &&
                     set_lds(k_scatter<false, 4>, scat) && set_lds(k_scatter<true, 4>, scat) &&
-                    set_lds(k_scan, scat) && set_lds(k_memo, memo_lds_bytes(f));
+                    set_lds(k_memo, memo_lds_bytes(f));
     return ok ? GR_OK : GR_ERR_HIP;
 }
 
@@ -1047,13 +1047,13 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     }
     {
         ProfScope ps(f, kScanRoute + off, s);
-        hipLaunchKernelGGL(k_scan, dim3(1), dim3(kScanBlock), scat_lds, s, f->len_cnt, f->len_base, f->row_len,
+        hipLaunchKernelGGL(k_scan, dim3(kScanGroups), dim3(kScanBlock), 0, s, f->len_cnt, f->len_base, f->row_len,
                            f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, out.n_selected, bins);
     }
     {
         ProfScope ps(f, kScatterRoute + off, s);
 #define GR_LAUNCH_SCATTER(M, I) hipLaunchKernelGGL((k_scatter<M, I>), dim3(blocks_for(I)), dim3(kGroupBlock), scat_lds, s, src, \
-                                                   f->len_base, f->rank, f->recs, out.inst, out.slack, bins, f->max_len, f->n_inst)
+                                                   f->len_cnt, f->len_base, f->rank, f->recs, out.inst, out.slack, bins, f->max_len, f->n_inst)
         (void)s_items;
         if (migrate) GR_LAUNCH_SCATTER(true, 4); else GR_LAUNCH_SCATTER(false, 4);
 #undef GR_LAUNCH_SCATTER
