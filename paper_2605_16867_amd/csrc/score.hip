@@ -1017,6 +1017,7 @@ int score_prepare(gr_fleet* f)
     const bool ok = set_lds(k_hist<false, 4>, hist) && set_lds(k_hist<true, 4>, hist) &&
                     set_lds(k_hist<false, 16>, hist) && set_lds(k_hist<true, 16>, hist) &&
                     set_lds(k_scatter<false, 4>, scat) && set_lds(k_scatter<true, 4>, scat) &&
+                    set_lds(k_scatter<false, 8>, scat) && set_lds(k_scatter<true, 8>, scat) &&
                     set_lds(k_memo, memo_lds_bytes(f));
     return ok ? GR_OK : GR_ERR_HIP;
 }
@@ -1032,7 +1033,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     // requests per workgroup of the grouping kernels.  Every workgroup pays a pass over all length
     // bins and one global atomic per length it has seen: the histogram of a large batch is faster
     // with few large workgroup shares, the scatter (which also writes the records) is not.
-    const int h_items = n > (int64_t(1) << 20) ? 16 : 4, s_items = 4;
+    const int h_items = n > (int64_t(1) << 20) ? 16 : 4, s_items = n > (int64_t(1) << 20) ? 8 : 4;
     const auto blocks_for = [n](int items) {
         return (unsigned)((n + (int64_t)kGroupBlock * items - 1) / ((int64_t)kGroupBlock * items));
     };
@@ -1054,8 +1055,8 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         ProfScope ps(f, kScatterRoute + off, s);
 #define GR_LAUNCH_SCATTER(M, I) hipLaunchKernelGGL((k_scatter<M, I>), dim3(blocks_for(I)), dim3(kGroupBlock), scat_lds, s, src, \
                                                    f->len_cnt, f->len_base, f->rank, f->recs, out.inst, out.slack, bins, f->max_len, f->n_inst)
-        (void)s_items;
-        if (migrate) GR_LAUNCH_SCATTER(true, 4); else GR_LAUNCH_SCATTER(false, 4);
+        if (migrate) { if (s_items == 8) GR_LAUNCH_SCATTER(true, 8); else GR_LAUNCH_SCATTER(true, 4); }
+        else { if (s_items == 8) GR_LAUNCH_SCATTER(false, 8); else GR_LAUNCH_SCATTER(false, 4); }
 #undef GR_LAUNCH_SCATTER
     }
     const int64_t max_rows = n < bins ? n : bins;
