@@ -221,7 +221,10 @@ struct MemoArgs {
     const uint16_t* tabR;
     const float2 *tabGH, *headGH;
     float* memo;
-    int n_inst, m_pad, cap;
+    float* grp_min;        // [m_pad / kMemoP][row_cap]
+    float2* grp_k;         // [m_pad / kMemoP]
+    const float2* posK;
+    int n_inst, m_pad, cap, row_cap;
     float keep;      // 1 - weight of the black-box estimate: scales the white-box curvature gamma
 };
 
@@ -240,6 +243,7 @@ struct MemoArgs {
 constexpr int kMemoBlock = kMemoP * kWave;
 constexpr int kMemoTile = kMemoU * (kMemoP + 1);       // floats
 static_assert(kMemoU == 4 * kWave, "a lane owns four consecutive counters");
+static_assert(kMemoP == 16, "a length's values of one workgroup sit in one row of 16 lanes");
 
 __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
 {
@@ -274,6 +278,17 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // the least delta and gamma of this workgroup's positions, for the scoring kernel's bounds
+    if (blockIdx.y == 0 && tid < kMemoP) {
+        float2 k = a.posK[p0 + tid];
+#pragma unroll
+        for (int d = 1; d < kMemoP; d <<= 1) {
+            k.x = fminf(k.x, __shfl_xor(k.x, d, kMemoP));
+            k.y = fminf(k.y, __shfl_xor(k.y, d, kMemoP));
+        }
+        if (tid == 0) a.grp_k[blockIdx.x] = k;
+    }
 
     // entries that belong to rows before the run (the rows are ascending with the entries: the
     // lanes that still find one form a prefix)
@@ -337,7 +352,26 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
         for (int it = 0; it < kMemoU * kMemoP / kMemoBlock; ++it) {
             const int ul = tid / kMemoP + (kMemoBlock / kMemoP) * it;
             const int u = u0 + ul;
-            if (u < U) a.memo[(size_t)u * a.m_pad + p0 + col] = tile[ul * (kMemoP + 1) + col];
+            const float e = tile[ul * (kMemoP + 1) + col];
+            if (u < U) a.memo[(size_t)u * a.m_pad + p0 + col] = e;
+            // the least of the row's kMemoP values (they sit in one row of 16 lanes), for the
+            // scoring kernel's walk in capability order
+            // running minimum along the row of 16 lanes (a lane without a source keeps its value):
+            // lane 15 ends with all 16.  Written out: the compiler pairs every DPP read with a
+            // move and a canonicalising maximum; the s_nops keep the distance a DPP read needs
+            // from the instruction that wrote its source.
+            float m = e;
+            asm volatile("s_nop 1\n\t"
+                         "v_min_f32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+                         "s_nop 1\n\t"
+                         "v_min_f32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+                         "s_nop 1\n\t"
+                         "v_min_f32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+                         "s_nop 1\n\t"
+                         "v_min_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
+                         "s_nop 1"
+                         : "+v"(m));
+            if (u < U && col == kMemoP - 1) a.grp_min[(size_t)blockIdx.x * a.row_cap + u] = m;
         }
     }
 }
@@ -348,6 +382,9 @@ struct TileArgs {
     const ReqRec* recs;
     const float* memo;     // [row][m_pad] E of (distinct length, position in capability order)
     const float2* posK;    // [m_pad] (delta, gamma) of the instance at each position
+    const float* grp_min;  // [m_pad / kMemoP][row_cap] least E of each run of kMemoP positions
+    const float2* grp_k;   // [m_pad / kMemoP] least delta and gamma of each run
+    int row_cap;
     int* out_inst;
     float* out_slack;
     uint8_t* out_fallback;
@@ -548,6 +585,9 @@ __device__ inline void tile_winners(const float (&minT)[kTileReq], float Tm, int
 
 struct RowView {
     const float* __restrict__ E;       // this length's row of the memo table
+    const float* __restrict__ grpE;    // least E of each run of kMemoP positions of the row, run r at grpE[r * grp_stride]
+    int grp_stride;
+    const float2* __restrict__ grpK;   // least delta and least gamma of each such run (LDS), or null
     const float2* __restrict__ posK;
     const int* __restrict__ order;
     float Lf;
@@ -613,9 +653,11 @@ __device__ inline void first_feasible_sparse(const RowView& rv, float rec_c0, fl
 
 // The same when many requests of the tile have a feasible instance: all
 // requests against each block, two vector operations per pair; a request that
-// is done (or never had one) carries D = -inf.
-__device__ inline void first_feasible_dense(const RowView& rv, const float (&c0)[kTileReq], float Dc,
-                                            unsigned long long fm, int lane, int& foundP, float& foundT)
+// is done (or never had one) carries D = -inf.  Looks at the first n_blocks
+// blocks and returns the requests still open after them.
+__device__ inline unsigned long long first_feasible_dense(const RowView& rv, const float (&c0)[kTileReq], float Dc,
+                                                          unsigned long long fm, int n_blocks, int lane, int& foundP,
+                                                          float& foundT)
 {
     float D[kTileReq];
 #pragma unroll
@@ -627,11 +669,11 @@ __device__ inline void first_feasible_dense(const RowView& rv, const float (&c0)
     constexpr int kChunk = 2;
     Chunk<kChunk, false> cur;
     load_chunk(rv, 0, lane, cur);
-    for (int b0 = 0; b0 < rv.nblk && left; b0 += kChunk) {
+    for (int b0 = 0; b0 < n_blocks && left; b0 += kChunk) {
         Chunk<kChunk, false> nxt;
         load_chunk(rv, b0 + kChunk, lane, nxt);
         __builtin_amdgcn_sched_barrier(0);
-        for (int i = 0; i < kChunk && b0 + i < rv.nblk && left; ++i) {
+        for (int i = 0; i < kChunk && b0 + i < n_blocks && left; ++i) {
             float e = 0.f;
             float2 kk = make_float2(0.f, 0.f);
 #pragma unroll
@@ -658,6 +700,67 @@ __device__ inline void first_feasible_dense(const RowView& rv, const float (&c0)
             }
         }
         cur = nxt;
+    }
+    return left;
+}
+
+// First feasible position in capability order by bounds: a run of kMemoP
+// consecutive positions cannot hold a feasible one unless
+// least E + c0 * (least delta + L * least gamma) <= D, and that bound is formed
+// with the same two fused multiply-adds as the latency itself, which are
+// monotone in every operand (c0, L >= 0), so it never exceeds the latency of a
+// position of the run as the main pass computed it.  The bound's two
+// request-independent parts are read once per tile (lane = run, 64 runs per
+// register pair; runs beyond kBoundRegs * 64 are read again per request).  Per
+// request: which runs pass, then from the first such run on 64 positions at
+// once until there is a hit.  Instances come slowest first, so most runs
+// before the answer fail the bound and are never looked at.
+constexpr int kBoundRegs = 4;
+constexpr int kRunsPerBlock = kWave / kMemoP;
+
+__device__ inline void first_feasible_bounded(const RowView& rv, float rec_c0, float Dc, unsigned long long fm,
+                                              int lane, int& foundP, float& foundT)
+{
+    const int ngrp = rv.nblk * kRunsPerBlock;
+    float gE[kBoundRegs], gK[kBoundRegs];
+#pragma unroll
+    for (int i = 0; i < kBoundRegs; ++i) {
+        const int g = min(i * kWave + lane, ngrp - 1);
+        gE[i] = i * kWave + lane < ngrp ? rv.grpE[(size_t)g * rv.grp_stride] : __builtin_inff();     // never passes
+        gK[i] = kappa_of(rv.grpK[g], rv.Lf);
+    }
+    while (fm) {
+        const int j = __ffsll((long long)fm) - 1;
+        fm &= fm - 1;
+        const float c0j = readlane_f(rec_c0, j), Dj = readlane_f(Dc, j);
+        bool found = false;
+        // looks at the 64 positions from run `gi` on; true when one of them is feasible
+        const auto visit = [&](int gi) {
+            const int p = gi * kMemoP + lane, pc = min(p, rv.nblk * kWave - 1);
+            const float T = fmaf(c0j, kappa_of(rv.posK[pc], rv.Lf), rv.E[pc]);
+            const unsigned long long hit = __ballot(p == pc && T <= Dj);
+            if (hit) {
+                const int fl = __ffsll((long long)hit) - 1;
+                const float Tf = readlane_f(T, fl);
+                if (lane == j) { foundP = gi * kMemoP + fl; foundT = Tf; }
+                found = true;
+            }
+        };
+        const auto chunk = [&](int g0, float boundE, float boundK) {
+            unsigned long long pass = __ballot(fmaf(c0j, boundK, boundE) <= Dj);
+            while (pass && !found) {
+                const int first = __ffsll((long long)pass) - 1;
+                pass &= ~(((1ull << kRunsPerBlock) - 1ull) << first);      // the runs this visit covers
+                visit(g0 + first);
+            }
+        };
+#pragma unroll
+        for (int i = 0; i < kBoundRegs; ++i)
+            if (!found && i * kWave < ngrp) chunk(i * kWave, gE[i], gK[i]);
+        for (int g0 = kBoundRegs * kWave; g0 < ngrp && !found; g0 += kWave) {
+            const int g = min(g0 + lane, ngrp - 1);
+            chunk(g0, g0 + lane < ngrp ? rv.grpE[(size_t)g * rv.grp_stride] : __builtin_inff(), kappa_of(rv.grpK[g], rv.Lf));
+        }
     }
 }
 
@@ -753,6 +856,7 @@ __device__ __forceinline__ void main_pass(const RowView& rv, const float (&c0)[k
 }
 
 constexpr int kSparseFeasible = 8;   // up to this many feasible requests of a tile go one by one
+constexpr int kDenseBlocks = 2;      // blocks looked at for all requests at once before the bounded walk
 
 // One wave per tile: up to kTileReq requests of one length against all
 // instances.  Lane = position in capability order within a block of 64; the
@@ -771,7 +875,8 @@ constexpr int kSparseFeasible = 8;   // up to this many feasible requests of a t
 // running minima, two sets of operands in flight and the epilogue's
 // temporaries fit without spilling).  With kW > 4 the workgroup first copies
 // the (delta, gamma) pairs of all positions, which every tile reads in full,
-// into LDS: 24 / kW workgroups of m_pad * 8 bytes share a compute unit, and the
+// into LDS (and their minima over runs of kMemoP positions, for the bounded
+// walk): 24 / kW workgroups of m_pad * 8.5 bytes share a compute unit, and the
 // texture path is left to the table rows and the gathers of the search for the
 // minimum.
 template <bool kWriteT, int kW>
@@ -788,8 +893,10 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     if ((int)(blockIdx.x >> 3) >= per_xcd) return;
     const int bid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     const int t = bid * kW + wave;
+    float2* lds_grpK = lds_posK + a.m_pad;      // least (delta, gamma) of each run of kMemoP positions
     if (kLdsK) {
         for (int p = threadIdx.x; p < a.m_pad; p += kW * kWave) lds_posK[p] = a.posK[p];
+        for (int g = threadIdx.x; g < a.m_pad / kMemoP; g += kW * kWave) lds_grpK[g] = a.grp_k[g];
         __syncthreads();
     }
     if (t >= NT) return;
@@ -819,6 +926,9 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
 
     RowView rv;
     rv.E = a.memo + (size_t)u * a.m_pad;
+    rv.grpE = a.grp_min + u;
+    rv.grp_stride = a.row_cap;
+    rv.grpK = kLdsK ? lds_grpK : nullptr;
     rv.posK = kLdsK ? lds_posK : a.posK;
     rv.order = a.order;
     rv.Lf = (float)a.row_len[u];
@@ -857,8 +967,15 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     float foundT = 0.f;
     const unsigned long long fm = __ballot(mine && Tm <= Dc);
     if (fm) {
-        if (__popcll(fm) <= kSparseFeasible) first_feasible_sparse(rv, rec.c0, Dc, fm, lane, foundP, foundT);
-        else first_feasible_dense(rv, c0, Dc, fm, lane, foundP, foundT);
+        // many feasible requests: most have their first feasible instance early or not at all
+        // early, so the first blocks are looked at for all of them at once; the rest by bounds
+        unsigned long long rest = fm;
+        if (__popcll(rest) > kSparseFeasible)
+            rest = first_feasible_dense(rv, c0, Dc, rest, kLdsK ? min(kDenseBlocks, rv.nblk) : rv.nblk, lane, foundP, foundT);
+        if (rest) {
+            if (kLdsK) first_feasible_bounded(rv, rec.c0, Dc, rest, lane, foundP, foundT);
+            else first_feasible_sparse(rv, rec.c0, Dc, rest, lane, foundP, foundT);
+        }
     }
 
     // ---- the others: which of the winning lane's positions has T = the minimum.  Lane l looks
@@ -1064,7 +1181,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         MemoArgs m{};
         m.totals = f->totals; m.row_len = f->row_len; m.len_ceil = f->len_ceil; m.order = f->order; m.hN = f->hN;
         m.cls = f->cls; m.inst_class = f->inst_class;
-        m.tabR = f->tabR; m.tabGH = f->tabGH; m.headGH = f->headGH; m.memo = f->memo;
+        m.tabR = f->tabR; m.tabGH = f->tabGH; m.headGH = f->headGH; m.memo = f->memo; m.grp_min = f->grp_min; m.grp_k = f->grp_k; m.posK = f->posK; m.row_cap = (int)f->row_cap;
         m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.cap = f->cap; m.keep = (float)(1.0 - f->lam_built);
         // every workgroup walks all lengths; with few instances the lengths are dealt out to several
         const int gx = f->m_pad / kMemoP;
@@ -1077,13 +1194,13 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     {
         TileArgs t{};
         t.totals = f->totals; t.row_len = f->row_len; t.row_off = f->row_off; t.tile_off = f->tile_off;
-        t.order = f->order; t.recs = f->recs; t.memo = f->memo; t.posK = f->posK;
+        t.order = f->order; t.recs = f->recs; t.memo = f->memo; t.posK = f->posK; t.grp_min = f->grp_min; t.grp_k = f->grp_k; t.row_cap = (int)f->row_cap;
         t.out_inst = out.inst; t.out_slack = out.slack; t.out_fallback = out.fallback; t.out_T = out.T;
         t.n_inst = f->n_inst; t.m_pad = f->m_pad;
         const int64_t max_tiles = (n + kTileReq - 1) / kTileReq + max_rows;
         // 24 waves per compute unit (6 per SIMD): the coefficient pairs go to LDS when the
         // 24 / kW workgroups resident together have room for a copy each
-        const size_t k_bytes = (size_t)f->m_pad * sizeof(float2);
+        const size_t k_bytes = (size_t)(f->m_pad + f->m_pad / kMemoP) * sizeof(float2);
         const int kw = k_bytes <= 49152 ? 8 : k_bytes <= 65536 ? 12 : 4;
         unsigned blocks = (unsigned)((max_tiles + kw - 1) / kw);
         blocks = (blocks + 7u) & ~7u;
