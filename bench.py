@@ -52,6 +52,11 @@ def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--blend", type=float, default=0.0,
+                    help="weight of the black-box status (Sec. 3.3) after three rounds of synthetic observations")
+    ap.add_argument("--batch-cap", action="store_true", help="per-instance caps on the decode batch (Sec. 3.1)")
+    ap.add_argument("--feedback-chunk", type=int, default=0,
+                    help="route the incoming batch with the status refreshed every so many requests")
     ap.add_argument("--latency-iters", type=int, default=100,
                     help="calls of gr_score_route timed one by one for the route-batch latency")
     ap.add_argument("--warmup", type=int, default=3)
@@ -151,10 +156,26 @@ def main():
     if a.prefixes > 0 and R:
         hits = [torch.from_numpy(x).to(dev) for x in workloads.cached_prefixes(fl, a.prefixes, seed=0)]
 
+    variant = []
+    if hits is not None:
+        variant.append(f"prefixes({a.prefixes:g}/request)")
+    if a.blend > 0:
+        for w, ow, op, od in workloads.observed_status(fl, rounds=3, seed=0):
+            h.gr_observe(w, *[torch.from_numpy(x).to(dev) for x in (ow, op, od)])
+        h.gr_set_blend(a.blend)
+        variant.append(f"blend({a.blend:g})")
+    if a.batch_cap:
+        h.gr_set_batch_cap(workloads.batch_caps(fl, seed=0))
+        variant.append("batch-cap")
+    if a.feedback_chunk > 0:
+        variant.append(f"feedback(chunk={a.feedback_chunk})")
+
     def step():
         h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"],
                           d["q_off"], d["q_prompt"], d["q_len"], fin)
-        if R and hits is None:
+        if R and a.feedback_chunk > 0:
+            h.gr_route_feedback(a.feedback_chunk, d["in_prompt"], d["in_len"], d["in_budget"], inst, slack)
+        elif R and hits is None:
             h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, slack)
         elif R:
             h.gr_score_route_cached(d["in_prompt"], d["in_len"], d["in_budget"], hits[0], hits[1], hits[2],
@@ -163,6 +184,8 @@ def main():
                        d["q_off"], d["q_prompt"], d["q_len"], d["act_budget"],
                        flag, fin2, tgt, tsl, nfl)
 
+    # launches of one step (the feedback variant repeats grouping, scoring and the status build per chunk)
+    prof_slots = 32 + (16 * (-(-R // a.feedback_chunk)) if a.feedback_chunk > 0 else 0)
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
@@ -170,7 +193,7 @@ def main():
     # (scoring tiles, status build); an event pair around each of the dozen short kernels as well
     # would cost about a tenth of the step
     h.gr_profile_select(["k_tile", "k_build"])
-    h.gr_profile_enable(32 * a.steps)
+    h.gr_profile_enable(prof_slots * a.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(a.steps):
@@ -180,7 +203,7 @@ def main():
     prof = h.gr_profile_read()
     # outside the timed region: the same steps with every kernel timed, for the breakdown
     h.gr_profile_select(None)
-    h.gr_profile_enable(32 * a.steps)
+    h.gr_profile_enable(prof_slots * a.steps)
     for _ in range(a.steps):
         step()
     torch.cuda.synchronize()
@@ -223,11 +246,11 @@ def main():
         avg_ms = ms / cnt
         k = {"avg_ms": avg_ms, "launches_per_step": cnt / a.steps}
         if name.startswith("k_tile"):
-            pairs = pairs_route if "route" in name else pairs_mig
+            pairs = (pairs_route if "route" in name else pairs_mig) / (cnt / a.steps)     # per launch
             k.update(bound="alu", pairs=pairs, pairs_per_s=pairs / (avg_ms * 1e-3),
                      achieved=pairs * OPS_PER_PAIR / (avg_ms * 1e-3) / 1e12,
                      peak=FP32_VECTOR_PEAK_TFLOPS, unit="TFLOP/s")
-        elif name == "k_build":
+        elif name == "k_build" and cnt == 2 * a.steps:
             # two launches per step: plain build, and the scan's rebuild with budget + flag
             by = entries * (BUILD_BYTES_PER_ENTRY + SCAN_EXTRA_BYTES_PER_ENTRY / 2)
             k.update(bound="hbm", achieved=by / (avg_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
@@ -248,7 +271,7 @@ def main():
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": a.config if hits is None else f"{a.config}+prefixes({a.prefixes:g}/request)",
+        "config": {"workload": "+".join([a.config] + variant),
                    "instances": M, "held_requests": entries,
                    "incoming": R, "flagged": n_flagged, "route_pairs": pairs_route,
                    "migration_pairs": pairs_mig},
@@ -261,7 +284,9 @@ def main():
             "p99": route_ms[min(len(route_ms) - 1, int(0.99 * len(route_ms)))]}
     # achieved HBM rate as a share of the 8 TB/s peak: the streaming kernel on its algorithmic
     # bytes, the dominant kernel on the bytes the hardware counters saw
-    out["hbm_pct_of_peak"] = {"k_build (algorithmic bytes)": 100.0 * kernels["k_build"]["frac"]}
+    out["hbm_pct_of_peak"] = {}
+    if "frac" in kernels["k_build"]:
+        out["hbm_pct_of_peak"]["k_build (algorithmic bytes)"] = 100.0 * kernels["k_build"]["frac"]
     if traffic is not None:
         out["hbm_pct_of_peak"][dominant + " (counter bytes)"] = (
             100.0 * traffic / (dk["avg_ms"] * 1e-3) / (HBM_PEAK_GBS * 1e9))
