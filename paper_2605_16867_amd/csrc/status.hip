@@ -210,11 +210,13 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     };
 
     // ---- batch cap (Sec. 3.1: concurrency bounded by memory).  With room for everybody and a
-    // newcomer nothing changes.  Otherwise the instance is played forward, event by event (the
-    // queue's head is admitted whenever the batch has room; between two departures the batch is
-    // fixed and its time is a closed form), up to the moment a newcomer would be admitted: q_g is
-    // that moment, and the requests still running then, with what is left of them, are what the
-    // closed form below is built on.  Requests that leave earlier get their finish time here.
+    // newcomer nothing changes.  Otherwise, while there is a queue, the instance is played forward
+    // event by event (the queue's head is admitted whenever the batch has room; between two
+    // departures the batch is fixed and its time is a closed form); requests that leave meanwhile
+    // get their finish time here.  Once the queue is empty only departures are left: if the batch
+    // has room now, a newcomer is admitted now (q_g = now, and the closed form below is built on
+    // what is running); if not, it is admitted after the departure that makes room, which the
+    // closed form itself gives (further down).
     // (kCapAware is a kernel of its own: the event loop's registers would cost the plain build a wave per SIMD)
     const int cap_g = kCapAware ? max(a.batch_cap[g], 1) : 0x7fffffff;
     const bool capped = kCapAware && cap_g <= N;
@@ -253,7 +255,7 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
                 t += cc.delta * (double)sumP;
                 n += k; C += sumP; next_q += k;
             }
-            if (next_q == N && n < cap_g) break;      // a newcomer would be admitted now
+            if (next_q == N) break;        // the queue is empty: what follows is departures only (below)
             // next departure
             int smin = 0x7fffffff;
 #pragma unroll
@@ -316,6 +318,93 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     }
     long long Ytot, Xtot, Ctot;
     long long Y = wave_excl_scan(yl, Ytot), X = wave_excl_scan(xl, Xtot), Pc = wave_excl_scan(cl, Ctot);
+
+    // ---- a full batch with an empty queue: a newcomer is admitted when the kstar-th of the running
+    // requests has left.  Until then nobody joins, so everybody's finish time is the closed form
+    // as it stands, the admission time q_g is the finish time of that request (s steps from now),
+    // and the table describes the others as they are then: s steps shorter, contexts s longer.
+    // With R' = R - s, c' = c + s over the survivors (positions vstar.. of the sorted order):
+    //   sum R' = sum R - m s,   sum (c' R' + tri(R')) = sum (c R + tri(R)) - s sum c - m tri(s),
+    //   sum c' = sum c + m s    (m terms each; all integers, exact)
+    if constexpr (kCapAware) {
+        if (capped && Nrun >= cap_g) {
+            const int kstar = Nrun - cap_g + 1;
+            long long Y1 = Y, X1 = X, P1 = Pc;
+            double q_adm = 0.0;
+            int sstar = 0;
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r) {
+                const int v = lane * kEPL + r;
+                const long long Rr = R[r], triR = (long long)(R[r] * (R[r] - 1) / 2);
+                Y1 += Rr; X1 += (long long)cx[r] * Rr + triR; P1 += cx[r];
+                if (v < Nrun) {
+                    const double n_after = (double)(Nrun - v - 1), S_next = (double)(Ctot - P1), Rd = (double)Rr;
+                    const double I1 = (double)Y1 + n_after * Rd;
+                    const double I2 = (double)X1 + Rd * S_next + n_after * (double)triR;
+                    const double fin = q + fma(cc.gamma, I2, fma(cc.beta, I1, cc.alpha * Rd));
+                    report(idx[r], fin, (double)olen[idx[r]], (double)octx[idx[r]]);
+                    if (v == kstar - 1) { q_adm = fin; sstar = R[r]; }
+                }
+            }
+            const int owner = (kstar - 1) / kEPL;
+            q_adm = __shfl(q_adm, owner, kWave);
+            sstar = __shfl(sstar, owner, kWave);
+            // those that have left by then (equal lengths leave together)
+            long long gone = 0, yg = 0, xg = 0, cg = 0;
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r)
+                if (lane * kEPL + r < Nrun && R[r] <= sstar) {
+                    ++gone; yg += R[r]; cg += cx[r];
+                    xg += (long long)cx[r] * R[r] + (long long)(R[r] * (R[r] - 1) / 2);
+                }
+            const int vstar = (int)wave_sum(gone);
+            const long long Ystar = wave_sum(yg), Xstar = wave_sum(xg), Pstar = wave_sum(cg);
+            const int Nleft = Nrun - vstar;
+            const long long s64 = sstar, tri_s = s64 * (s64 - 1) / 2;
+            Y1 = Y; X1 = X; P1 = Pc;
+            uint16_t* dstR = a.tabR + (size_t)g * kCap;
+            float2* dstGH = a.tabGH + (size_t)g * kCap;
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r) {
+                const int v = lane * kEPL + r;
+                const long long Rr = R[r];
+                Y1 += Rr; X1 += (long long)cx[r] * Rr + (long long)(R[r] * (R[r] - 1) / 2); P1 += cx[r];
+                if (v >= vstar && v < Nrun) {
+                    const int w = v - vstar;                      // position among the survivors
+                    const long long m = w + 1;
+                    const double Ys = (double)((Y1 - Ystar) - m * s64);
+                    const double Xs = (double)((X1 - Xstar) - s64 * (P1 - Pstar) - m * tri_s);
+                    const double n_after = (double)(Nleft - w - 1);
+                    const double S_next = (double)((Ctot - P1) + (long long)(Nleft - w - 1) * s64);
+                    double Gq = q_adm + (cc.beta * Ys + cc.gamma * Xs);
+                    double Hs = cc.alpha + (cc.beta * (n_after + 1.0) + cc.gamma * S_next);
+                    if (blended) { Gq = keep * Gq + a.lam * bq; Hs = keep * Hs + a.lam * bd; }
+                    dstR[w] = (uint16_t)(R[r] - sstar);
+                    dstGH[w] = make_float2((float)Gq, (float)Hs);
+                } else {                                          // the slots behind the survivors
+                    const int slot = v < Nrun ? Nleft + v : v;
+                    dstR[slot] = (uint16_t)0xFFFFu;
+                    dstGH[slot] = make_float2(0.f, 0.f);
+                }
+            }
+            if (lane == 0) {
+                const double Cd = (double)((Ctot - Pstar) + (long long)Nleft * s64);
+                double Gq0 = q_adm, H0 = cc.alpha + (cc.beta * (double)(Nleft + 1) + cc.gamma * Cd);
+                if (blended) { Gq0 = keep * Gq0 + a.lam * bq; H0 = keep * H0 + a.lam * bd; }
+                a.headGH[g] = make_float2((float)Gq0, (float)H0);
+                a.hN[g] = Nleft;
+                a.rank_acc[g] = 0;
+                if (!a.use_pending) a.pend_cnt[g] = 0;
+                // the next decode step that runs: the first one played above, else the batch as it stands
+                double d = d_first >= 0.0 ? d_first
+                                          : fma(cc.gamma, (double)Ctot, fma(cc.beta, (double)Nrun, cc.alpha));
+                if (blended) d = keep * d + a.lam * bd;
+                a.hD[g] = d;
+                if (a.out_d) a.out_d[g] = d;
+            }
+            return;
+        }
+    }
 
     // table entry v describes the segment after the v+1 shortest requests, n of them still running:
     //   E_g(L) = Gq + L * H + tri(L) * gamma * (n + 1)

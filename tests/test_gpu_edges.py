@@ -159,6 +159,27 @@ def test_wide_fleets(n_inst):
     assert rep["finish_rel_err"] < 1e-6
 
 
+def test_batch_cap_departures_in_groups():
+    """Full batches whose departures come in groups of equal lengths: the one that
+    makes room for a newcomer takes its whole group along (down to an empty batch),
+    with and without a queue in front."""
+    rng = np.random.default_rng(17)
+    def ent(lens):
+        lens = np.asarray(lens)
+        return np.stack([rng.integers(128, 2049, len(lens)), rng.integers(0, 201, len(lens)), lens], 1)
+    acts = [ent([50] * 20), ent([5] * 4 + [9] * 4 + [30] * 4), ent([7, 7, 7, 12, 12, 40]), ent([3] * 6),
+            ent(rng.integers(1, 60, 300)), np.zeros((0, 3))]
+    queued = [[], [], [(500, 20), (300, 7), (900, 7), (128, 33), (700, 5)], [(400, 3), (400, 3)],
+              [(int(p), int(l)) for p, l in zip(rng.integers(128, 2049, 40), rng.integers(1, 60, 40))], [(256, 9)]]
+    inc = np.stack([rng.integers(128, 2049, 200), rng.integers(1, 120, 200)], 1)
+    for caps in ([10, 7, 4, 2, 200, 1], [1, 12, 6, 6, 340, 3], [20, 1, 1, 8, 100, 1]):
+        fl = fleet([0, 1, 2, 0, 1, 2], acts, queued, inc, rng.uniform(0.5, 40, 200) * solo(inc[:, 0], inc[:, 1]))
+        fl.batch_cap = np.asarray(caps, dtype=np.int32)
+        sim = oracle.simulate(fl)
+        fl.act_budget = (sim.act_finish * rng.uniform(0.7, 1.3, len(sim.act_finish))).astype(np.float32)
+        parity.run_and_check(fl)
+
+
 def test_special_budgets():
     rng = np.random.default_rng(4)
     acts = [rand_entries(rng, 200) for _ in range(9)]
