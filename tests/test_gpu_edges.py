@@ -326,3 +326,56 @@ def test_cached_prefixes_decide_when_prefill_dominates():
     ex = rng.integers(-1, M, n).astype(np.int32)
     rep = parity.run_and_check(fl, exclude=ex, hits=hits)
     assert rep["route_moved_by_hits"] > n // 10
+
+
+def _random_case(rng):
+    """A small fleet with everything drawn at random: size, classes and their
+    coefficients, occupancy (idle instances included), queues, the mix of
+    lengths of the incoming batch, deadline scale, and which of the optional
+    inputs (exclusions, cached prefixes, observed status + blend, batch caps)
+    are present."""
+    M = int(rng.choice([1, 2, 3, 17, 64, 65, 130, 300]))
+    n_class = int(rng.integers(1, 6))
+    classes = [(2e-5 * f, 0.012 * f, 2e-4 * f, 2e-8 * f) for f in rng.uniform(0.5, 6.0, n_class)]
+    max_len = int(rng.choice([64, 4096, 32767]))
+    occ = rng.integers(0, 90, M) * (rng.random(M) > 0.15)
+    acts = [np.stack([rng.integers(1, 3000, n), rng.integers(0, 300, n),
+                      np.clip(np.rint(rng.lognormal(rng.uniform(1, 6), 1, n)), 1, max_len)], 1) if n else np.zeros((0, 3))
+            for n in occ]
+    queued = [[(int(p), int(l)) for p, l in zip(rng.integers(1, 3000, n), rng.integers(1, min(max_len, 500) + 1, n))]
+              for n in rng.integers(0, 6, M) * (rng.random(M) > 0.5)]
+    R = int(rng.choice([1, 5, 33, 200, 700]))
+    kinds = int(rng.choice([1, 3, 40, R]))
+    pool = np.clip(np.rint(rng.lognormal(rng.uniform(1, 6), 1.2, kinds)), 1, max_len)
+    inc = np.stack([rng.integers(1, 4000, R), rng.choice(pool, R)], 1)
+    c0 = classes[0]
+    bud = rng.uniform(0.3, 3, R) * float(rng.choice([0.5, 3, 20, 300])) * solo(inc[:, 0], inc[:, 1], c0)
+    special = rng.random(R)
+    bud = np.where(special < 0.03, 0.0, np.where(special < 0.06, np.inf, np.where(special < 0.08, -1.0, bud)))
+    fl = fleet(rng.integers(0, n_class, M), acts, queued, inc, bud, classes=classes, max_len=max_len)
+    fl.n_inst = M
+    sim = oracle.simulate(fl)
+    fl.act_budget = (sim.act_finish * rng.uniform(0.6, 1.4, len(sim.act_finish))).astype(np.float32)
+    fl.act_rem_refreshed = np.clip(np.rint(fl.act_rem * rng.lognormal(0, 0.4, len(fl.act_rem))), 1, max_len).astype(np.int32)
+    kw = {}
+    if rng.random() < 0.5:
+        kw["exclude"] = rng.integers(-1, M, R).astype(np.int32)
+    if rng.random() < 0.4:
+        kw["hits"] = workloads.cached_prefixes(fl, mean_hits=float(rng.uniform(0.5, 3)), seed=int(rng.integers(1 << 30)))
+    if rng.random() < 0.4:
+        kw["blackbox"] = (workloads.observed_status(fl, int(rng.integers(1, 4)), seed=int(rng.integers(1 << 30))),
+                          float(rng.choice([0.2, 0.5, 1.0])))
+    if rng.random() < 0.4:
+        fl.batch_cap = workloads.batch_caps(fl, 0.3, 1.3, seed=int(rng.integers(1 << 30)))
+    return fl, kw
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_small_fleets(seed):
+    rng = np.random.default_rng(1000 + seed)
+    for case in range(12):
+        fl, kw = _random_case(rng)
+        print(f"seed {seed} case {case}: M={len(fl.inst_class)} R={len(fl.in_prompt)} "
+              f"entries={len(fl.act_prompt)}+{len(fl.q_prompt)} options={sorted(kw)} "
+              f"cap={getattr(fl, 'batch_cap', None) is not None}", flush=True)
+        parity.run_and_check(fl, seed=seed, **kw)
