@@ -273,6 +273,25 @@ int gr_set_blend(gr_fleet* f, double black_box_weight);
 int gr_set_batch_cap(gr_fleet* f, const int32_t* cap);
 
 /*
+ * How a batch is scored.  Alg. 1 is the same either way; the work is laid out
+ * differently.  A large batch is grouped by predicted length, the decode term
+ * of Eq. 2 is tabulated once per (distinct length, instance), and tiles of 32
+ * requests run against all instances.  A batch of a few requests (the paper
+ * routes one arriving request at a time) skips grouping and table: a thread
+ * per (request, instance) pair finds its own segment by binary search.
+ *
+ *   max_pairs   gr_score_route and gr_route_feedback score a batch (a chunk)
+ *               pair by pair when n_req * (n_inst rounded up to 128) is at
+ *               most this and n_req <= 4096.  0: never.  Default 262 144.
+ * gr_score_route_cached and gr_risk_scan always take the grouped path.
+ * Equal latencies: pair by pair the lowest instance index wins; the grouped
+ * path prefers the earlier position in capability order among positions 64
+ * apart (the two differ only for instances of different speed with
+ * bit-identical latency).
+ */
+int gr_set_small_batch_pairs(gr_fleet* f, int64_t max_pairs);
+
+/*
  * Synchronises the device and returns the OR of the GR_DEV_* bits raised by
  * kernels since gr_create (HOST int32 out).  Not for the hot path.
  */

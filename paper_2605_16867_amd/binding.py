@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libgoodroute.so")
 
 EXPORTS = ("gr_create", "gr_destroy", "gr_build_status", "gr_score_route", "gr_score_route_cached", "gr_route_feedback",
-           "gr_risk_scan", "gr_observe", "gr_set_blend", "gr_set_batch_cap",
+           "gr_risk_scan", "gr_observe", "gr_set_blend", "gr_set_batch_cap", "gr_set_small_batch_pairs",
            "gr_device_status", "gr_strerror", "gr_profile_enable", "gr_profile_select", "gr_profile_read",
            "gr_profile_kernel_count", "gr_profile_kernel_name")
 
@@ -52,6 +52,8 @@ def lib() -> C.CDLL:
         l.gr_observe.argtypes = [p, C.c_double, p, p, p, p]
         l.gr_set_blend.restype = C.c_int
         l.gr_set_blend.argtypes = [p, C.c_double]
+        l.gr_set_small_batch_pairs.restype = C.c_int
+        l.gr_set_small_batch_pairs.argtypes = [p, C.c_int64]
         l.gr_set_batch_cap.restype = C.c_int
         l.gr_set_batch_cap.argtypes = [p, p]
         l.gr_device_status.restype = C.c_int
@@ -199,6 +201,9 @@ class Fleet:
 
     def gr_set_blend(self, black_box_weight: float) -> None:
         _check(lib().gr_set_blend(self._h, float(black_box_weight)), "gr_set_blend")
+
+    def gr_set_small_batch_pairs(self, max_pairs: int) -> None:
+        _check(lib().gr_set_small_batch_pairs(self._h, int(max_pairs)), "gr_set_small_batch_pairs")
 
     def gr_set_batch_cap(self, cap) -> None:
         """cap: host int array of n_inst entries, or None to remove the caps."""

@@ -12,7 +12,7 @@ const char* const kKernelNames[kNumKernels] = {
     "k_build", "k_rank_count", "k_rank_final",
     "k_hist<route>", "k_scan<route>", "k_scatter<route>", "k_memo<route>", "k_tile<route>",
     "k_hist<migrate>", "k_scan<migrate>", "k_scatter<migrate>", "k_memo<migrate>", "k_tile<migrate>",
-    "k_hits<route>"};
+    "k_hits<route>", "k_direct", "k_direct_finish"};
 
 template <typename T>
 bool dev_alloc(T** p, size_t n)
@@ -86,13 +86,14 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         dev_alloc(&f->emaQ, n_inst) && dev_alloc(&f->emaP, n_inst) && dev_alloc(&f->emaD, n_inst) &&
         dev_alloc(&f->rank_acc, n_inst) && dev_alloc(&f->rank, n_inst) && dev_alloc(&f->order, f->m_pad) && dev_alloc(&f->posK, f->m_pad) &&
         dev_alloc(&f->act_inst, f->max_active) && dev_alloc(&f->counters, 1) &&
-        dev_alloc(&f->pend_cnt, n_inst) && dev_alloc(&f->pend_prompt, tab) && dev_alloc(&f->pend_len, tab) &&
+        dev_alloc(&f->pend_cnt, n_inst) && dev_alloc(&f->pend_touched, n_inst) && dev_alloc(&f->pend_prompt, tab) && dev_alloc(&f->pend_len, tab) &&
         dev_alloc(&f->scratch_finish, f->max_active) && dev_alloc(&f->batch_cap, n_inst) &&
         dev_alloc(&f->len_cnt, f->bins) && dev_alloc(&f->len_base, f->bins) &&
         dev_alloc(&f->row_len, f->row_cap) && dev_alloc(&f->row_off, f->row_cap + 1) &&
         dev_alloc(&f->tile_off, f->row_cap + 1) && dev_alloc(&f->len_row, f->bins) && dev_alloc(&f->len_ceil, f->bins) && dev_alloc(&f->totals, 4) &&
         dev_alloc(&f->recs, f->req_cap) && dev_alloc(&f->memo, (size_t)f->row_cap * f->m_pad) &&
-        dev_alloc(&f->grp_min, (size_t)f->row_cap * (f->m_pad / kMemoP)) && dev_alloc(&f->grp_k, f->m_pad / kMemoP);
+        dev_alloc(&f->grp_min, (size_t)f->row_cap * (f->m_pad / kMemoP)) && dev_alloc(&f->grp_k, f->m_pad / kMemoP) &&
+        dev_alloc(&f->direct_best, 2 * (size_t)kDirectMax);
     if (!ok) { gr_destroy(f); return GR_ERR_NOMEM; }
 
     ClassCoef* host = static_cast<ClassCoef*>(malloc(sizeof(ClassCoef) * n_class));
@@ -104,8 +105,10 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
     const hipError_t e4 = hipMemset(f->len_cnt, 0, sizeof(int) * f->bins);
     const hipError_t e5 = hipMemset(f->totals, 0, sizeof(int) * 4);
     const hipError_t e6 = hipMemset(f->pend_cnt, 0, sizeof(int) * n_inst);
+    const hipError_t e8 = hipMemset(f->pend_touched, 0, sizeof(int) * n_inst);
+    const hipError_t e7 = hipMemset(f->direct_best, 0xFF, sizeof(unsigned long long) * 2 * kDirectMax);
     free(host);
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess || e6 != hipSuccess ||
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess || e6 != hipSuccess || e7 != hipSuccess || e8 != hipSuccess ||
         hipDeviceSynchronize() != hipSuccess) {
         gr_destroy(f);
         return GR_ERR_HIP;
@@ -120,9 +123,9 @@ int gr_destroy(gr_fleet* f)
     if (!f) return GR_OK;
     (void)hipDeviceSynchronize();
     void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabGH, f->headGH, f->hN, f->hD, f->emaQ, f->emaP, f->emaD, f->rank_acc,
-                    f->rank, f->order, f->posK, f->act_inst, f->pend_cnt, f->pend_prompt, f->pend_len,
+                    f->rank, f->order, f->posK, f->act_inst, f->pend_cnt, f->pend_touched, f->pend_prompt, f->pend_len,
                     f->scratch_finish, f->batch_cap, f->counters, f->len_cnt, f->len_base, f->row_len,
-                    f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, f->recs, f->memo, f->grp_min, f->grp_k};
+                    f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, f->recs, f->memo, f->grp_min, f->grp_k, f->direct_best};
     int rc = GR_OK;
     for (void* p : ptrs)
         if (p && hipFree(p) != hipSuccess) rc = GR_ERR_HIP;
@@ -151,9 +154,12 @@ int gr_build_status(gr_fleet* f, const int32_t* act_off, const int32_t* act_prom
     return launch_status(f, in, static_cast<hipStream_t>(hip_stream));
 }
 
-int gr_score_route(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_t* pred_len,
-                   const float* budget, const int32_t* exclude_inst, int32_t* out_inst,
-                   float* out_slack, uint8_t* out_fallback, float* out_T, void* hip_stream)
+namespace {
+// gr_score_route; `small_batch_ok`: a batch of a few requests may be scored pair by pair,
+// which leaves no table of per-length values behind
+int score_route(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_t* pred_len,
+                const float* budget, const int32_t* exclude_inst, int32_t* out_inst,
+                float* out_slack, uint8_t* out_fallback, float* out_T, void* hip_stream, bool small_batch_ok)
 {
     if (!f || n_req < 0) return GR_ERR_INVALID_ARG;
     if (!f->has_status) return GR_ERR_NO_STATUS;
@@ -165,7 +171,16 @@ int gr_score_route(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_
     src.n = n_req;
     ScoreOut o{};
     o.inst = out_inst; o.slack = out_slack; o.fallback = out_fallback; o.T = out_T;
-    return launch_score(f, src, false, o, static_cast<hipStream_t>(hip_stream));
+    return launch_score(f, src, false, o, static_cast<hipStream_t>(hip_stream), small_batch_ok);
+}
+}  // namespace
+
+int gr_score_route(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_t* pred_len,
+                   const float* budget, const int32_t* exclude_inst, int32_t* out_inst,
+                   float* out_slack, uint8_t* out_fallback, float* out_T, void* hip_stream)
+{
+    return score_route(f, n_req, ctx0, pred_len, budget, exclude_inst, out_inst, out_slack, out_fallback, out_T,
+                       hip_stream, true);
 }
 
 int gr_score_route_cached(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_t* pred_len,
@@ -176,8 +191,9 @@ int gr_score_route_cached(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const
 {
     if (n_hits < 0 || (n_req > 0 && !hit_off) || (n_hits > 0 && (!hit_inst || !hit_len)))
         return GR_ERR_INVALID_ARG;
-    const int rc = gr_score_route(f, n_req, ctx0, pred_len, budget, exclude_inst, out_inst, out_slack,
-                                  out_fallback, out_T, hip_stream);
+    // (the correction below reads the per-length table of the grouped pass)
+    const int rc = score_route(f, n_req, ctx0, pred_len, budget, exclude_inst, out_inst, out_slack,
+                               out_fallback, out_T, hip_stream, false);
     if (rc != GR_OK || n_req == 0) return rc;
     ReqSrc src{};
     src.ctx0 = ctx0; src.pred_len = pred_len; src.budget = budget; src.exclude = exclude_inst;
@@ -211,8 +227,11 @@ int gr_route_feedback(gr_fleet* f, int64_t n_req, int64_t chunk, const int32_t* 
         src.n = n;
         ScoreOut o{};
         o.inst = out_inst + s0; o.slack = out_slack + s0; o.fallback = out_fallback ? out_fallback + s0 : nullptr;
-        int rc = launch_score(f, src, false, o, s);
+        int rc = launch_score(f, src, false, o, s, true);
         if (rc == GR_OK) rc = launch_commit(f, n, out_inst + s0, ctx0 + s0, pred_len + s0, s);
+        // instances that were given nothing keep their tables, unless those are from an earlier blend
+        // weight or earlier caps
+        in.only_touched = f->tables_current ? 1 : 0;
         if (rc == GR_OK) rc = launch_status(f, in, s);
         if (rc != GR_OK) return rc;
     }
@@ -255,6 +274,7 @@ int gr_observe(gr_fleet* f, double weight, const float* obs_wait, const float* o
 {
     if (!f || !(weight >= 0.0 && weight <= 1.0)) return GR_ERR_INVALID_ARG;
     if (!obs_wait && !obs_prefill && !obs_decode) return GR_OK;
+    f->tables_current = false;      // (a blended table holds the smoothed status)
     return launch_ema(f, weight, obs_wait, obs_prefill, obs_decode, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -263,12 +283,21 @@ int gr_set_blend(gr_fleet* f, double black_box_weight)
     if (!f || !(black_box_weight >= 0.0 && black_box_weight <= 1.0)) return GR_ERR_INVALID_ARG;
     if (black_box_weight > 0.0 && !(f->have_q && f->have_p && f->have_d)) return GR_ERR_NO_STATUS;
     f->lam = black_box_weight;
+    f->tables_current = false;
+    return GR_OK;
+}
+
+int gr_set_small_batch_pairs(gr_fleet* f, int64_t max_pairs)
+{
+    if (!f || max_pairs < 0) return GR_ERR_INVALID_ARG;
+    f->small_batch_pairs = max_pairs;
     return GR_OK;
 }
 
 int gr_set_batch_cap(gr_fleet* f, const int32_t* cap)
 {
     if (!f) return GR_ERR_INVALID_ARG;
+    f->tables_current = false;
     if (!cap) { f->has_cap = false; return GR_OK; }
     for (int g = 0; g < f->n_inst; ++g)
         if (cap[g] < 1) return GR_ERR_INVALID_ARG;

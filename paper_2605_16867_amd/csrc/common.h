@@ -39,6 +39,7 @@ constexpr int kMaxLen = 32767;     // one LDS counter per length in the grouping
 constexpr int kTileReq = 32;       // requests of one length scored together by one wave
 constexpr int kGroupBlock = 1024;  // threads per workgroup of the grouping kernels (their cost is the pass over the LDS bins)
 constexpr int kMemoU = 256;        // lengths per pass of a workgroup of the memo kernel
+constexpr int kDirectMax = 4096;   // most requests of a batch scored pair by pair, without grouping
 constexpr int kMemoP = 16;         // instances (waves) per workgroup of the memo kernel
 
 struct ClassCoef {
@@ -75,7 +76,8 @@ struct ScoreOut {
 
 enum KernelId {
     kBuild = 0, kRankCount, kRankFinal, kHistRoute, kScanRoute, kScatterRoute, kMemoRoute, kTileRoute,
-    kHistMigrate, kScanMigrate, kScatterMigrate, kMemoMigrate, kTileMigrate, kHitsRoute, kNumKernels
+    kHistMigrate, kScanMigrate, kScatterMigrate, kMemoMigrate, kTileMigrate, kHitsRoute, kDirect, kDirectFinish,
+    kNumKernels
 };
 
 struct Profiler {
@@ -95,6 +97,7 @@ struct StatusIn {
     int* out_rank;
     uint8_t* out_flag;
     int use_pending = 0;      // count the requests routed since the caller's status (feedback routing)
+    int only_touched = 0;     // rebuild only the instances that have been given requests since the last build
 };
 
 }  // namespace gr
@@ -154,6 +157,10 @@ struct gr_fleet {
     float* memo = nullptr;       // [row_cap][m_pad] E per distinct length and position
     float* grp_min = nullptr;    // [m_pad / kMemoP][row_cap] least E of each run of kMemoP positions, per row
     float2* grp_k = nullptr;     // [m_pad / kMemoP] least delta and least gamma of each run
+    bool tables_current = false;   // every instance's table is from the last inputs, blend weight and caps
+    int* pend_touched = nullptr;   // [M] 1: given requests since its table was built
+    int64_t small_batch_pairs = int64_t(1) << 18;   // largest batch, in pairs, scored pair by pair
+    unsigned long long* direct_best = nullptr;   // [2][kDirectMax] running selections of a small batch (all ones between calls)
 };
 
 namespace gr {
@@ -185,7 +192,8 @@ int launch_ema(gr_fleet* f, double w, const float* s_q, const float* s_p, const 
 // score.hip
 size_t score_lds_bytes(const gr_fleet* f);
 int score_prepare(gr_fleet* f);
-int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& out, hipStream_t s);
+int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& out, hipStream_t s,
+                 bool small_batch_ok = false);
 int launch_hits(gr_fleet* f, const ReqSrc& src, const int* hit_off, const int* hit_inst, const int* hit_len,
                 int64_t n_hits, const ScoreOut& out, hipStream_t s);
 

@@ -1106,6 +1106,111 @@ __global__ __launch_bounds__(kBlock) void k_hits(HitArgs a)
     if (a.out_fallback) a.out_fallback[r] = !found;
 }
 
+// ------------------------------------------------------------------ small batches, pair by pair
+struct DirectArgs {
+    const int *ctx0, *pred_len;
+    const float* budget;
+    const int* exclude;
+    const int *order, *hN;
+    const ClassCoef* cls;
+    const int* inst_class;
+    const uint16_t* tabR;
+    const float2 *tabGH, *headGH, *posK;
+    unsigned long long *best_feasible, *best_any;     // [n] each, all ones on entry
+    int* out_inst;
+    float* out_slack;
+    uint8_t* out_fallback;
+    float* out_T;
+    int n, n_inst, m_pad, cap, max_len;
+    float keep;
+};
+
+// a float as an unsigned integer of the same order
+__device__ inline uint32_t ordered_bits(float v)
+{
+    const uint32_t b = __float_as_uint(v);
+    return b ^ ((b >> 31) ? 0xFFFFFFFFu : 0x80000000u);
+}
+
+__device__ inline float from_ordered_bits(uint32_t u)
+{
+    return __uint_as_float(u ^ ((u >> 31) ? 0x80000000u : 0xFFFFFFFFu));
+}
+
+// A batch of a few requests (one arriving request is the paper's own case):
+// grouping by length and a table of per-length values would cost more than
+// they save, so every pair gets a thread, which finds its segment by a binary
+// search over the instance's sorted lengths (Eq. 2's decode term in closed
+// form, the same expression as in the memo kernel) and forms T = E + c0 * kappa.
+// Thread = position in capability order, blockIdx.y = request.  Alg. 1's two
+// selections are two 64-bit minima per request, reduced over the wave and then
+// with one atomic each: (position, T) over the feasible pairs, i.e. the first
+// feasible instance in capability order, and (T, instance index) over all, i.e.
+// the least latency with ties to the lowest index.
+__global__ __launch_bounds__(kBlock) void k_direct(DirectArgs a)
+{
+    const int p = blockIdx.x * kBlock + threadIdx.x, r = blockIdx.y;
+    const int L = min(max(a.pred_len[r], 0), a.max_len);
+    const float c0 = (float)a.ctx0[r], Lf = (float)L, D = a.budget[r];
+    const float Dc = D > FLT_MAX ? FLT_MAX : D;       // padded positions hold +inf and stay infeasible
+    const int ex = a.exclude ? a.exclude[r] : -1;
+    const int g = p < a.m_pad ? a.order[p] : -1;
+    unsigned long long feas = ~0ull, any = ~0ull;
+    if (g >= 0) {
+        const int N = a.hN[g];
+        const uint16_t* __restrict__ R = a.tabR + (size_t)g * a.cap;
+        int k = 0;                                    // #{R_i <= L}
+        for (int step = a.cap; step >= 1; step >>= 1) {
+            const int probe = k + step;
+            if (probe <= N && (int)R[probe - 1] <= L) k = probe;
+        }
+        const float2 gh = k > 0 ? a.tabGH[(size_t)g * a.cap + k - 1] : a.headGH[g];
+        const float gam = a.keep * (float)a.cls[a.inst_class[g]].gamma;
+        const float tri = Lf * (Lf - 1.0f) * 0.5f;
+        const float E = fmaf(Lf, gh.y, gh.x) + tri * (gam * (float)(N - k + 1));
+        const float T = fmaf(c0, kappa_of(a.posK[p], Lf), E);
+        if (a.out_T) a.out_T[(size_t)r * a.n_inst + g] = T;
+        if (g != ex) {
+            const unsigned long long tb = ordered_bits(T);
+            any = (tb << 32) | (unsigned)g;
+            if (T <= Dc) feas = ((unsigned long long)p << 32) | tb;
+        }
+    }
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) {
+        const unsigned long long f2 = __shfl_xor(feas, d, kWave), a2 = __shfl_xor(any, d, kWave);
+        feas = f2 < feas ? f2 : feas;
+        any = a2 < any ? a2 : any;
+    }
+    if (lane_id() == 0) {
+        if (feas != ~0ull) atomicMin(&a.best_feasible[r], feas);
+        if (any != ~0ull) atomicMin(&a.best_any[r], any);
+    }
+}
+
+// The two selections of each request into Alg. 1's answer; they are set back to all ones.
+__global__ __launch_bounds__(kBlock) void k_direct_finish(DirectArgs a)
+{
+    const int r = blockIdx.x * kBlock + threadIdx.x;
+    if (r >= a.n) return;
+    const unsigned long long feas = a.best_feasible[r], any = a.best_any[r];
+    a.best_feasible[r] = ~0ull;
+    a.best_any[r] = ~0ull;
+    const bool found = feas != ~0ull;
+    int g = -1;
+    float T = 0.f;
+    if (found) {
+        g = a.order[(int)(feas >> 32)];
+        T = from_ordered_bits((uint32_t)feas);
+    } else if (any != ~0ull) {
+        g = (int)(uint32_t)any;
+        T = from_ordered_bits((uint32_t)(any >> 32));
+    }
+    a.out_inst[r] = g;
+    a.out_slack[r] = g >= 0 ? a.budget[r] - T : 0.f;
+    if (a.out_fallback) a.out_fallback[r] = !found;
+}
+
 __global__ void k_set_int(int* p, int v) { *p = v; }
 
 template <typename K>
@@ -1139,11 +1244,33 @@ int score_prepare(gr_fleet* f)
     return ok ? GR_OK : GR_ERR_HIP;
 }
 
-int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& out, hipStream_t s)
+int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& out, hipStream_t s,
+                 bool small_batch_ok)
 {
     const int64_t n = src.n;
     if (n == 0) {
         if (out.n_selected) hipLaunchKernelGGL(k_set_int, dim3(1), dim3(1), 0, s, out.n_selected, 0);
+        return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
+    }
+    // up to about two million pairs (the default) a thread per pair is cheaper than the five kernels
+    // of the grouped pass
+    if (small_batch_ok && !migrate && n <= kDirectMax && n * f->m_pad <= f->small_batch_pairs) {
+        DirectArgs d{};
+        d.ctx0 = src.ctx0; d.pred_len = src.pred_len; d.budget = src.budget; d.exclude = src.exclude;
+        d.order = f->order; d.hN = f->hN; d.cls = f->cls; d.inst_class = f->inst_class;
+        d.tabR = f->tabR; d.tabGH = f->tabGH; d.headGH = f->headGH; d.posK = f->posK;
+        d.best_feasible = f->direct_best; d.best_any = f->direct_best + kDirectMax;
+        d.out_inst = out.inst; d.out_slack = out.slack; d.out_fallback = out.fallback; d.out_T = out.T;
+        d.n = (int)n; d.n_inst = f->n_inst; d.m_pad = f->m_pad; d.cap = f->cap; d.max_len = f->max_len;
+        d.keep = (float)(1.0 - f->lam_built);
+        {
+            ProfScope ps(f, kDirect, s);
+            hipLaunchKernelGGL(k_direct, dim3((f->m_pad + kBlock - 1) / kBlock, (unsigned)n), dim3(kBlock), 0, s, d);
+        }
+        {
+            ProfScope ps(f, kDirectFinish, s);
+            hipLaunchKernelGGL(k_direct_finish, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, d);
+        }
         return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
     }
     const int bins = f->bins;

@@ -40,6 +40,8 @@ struct BuildArgs {
     int* pend_cnt;
     const int *pend_prompt, *pend_len;
     int use_pending;     // 0: a fresh status from the caller, the lists are emptied
+    int* pend_touched;   // 1: given requests since its table was built
+    int only_touched;    // leave the instances with a 0 there as they are
     const int* batch_cap;   // per instance: requests that may decode together; null = no bound
     // blend with the smoothed black-box status (Sec. 3.3): weight lam on it, 0 = none
     double lam;
@@ -142,6 +144,14 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int g = blockIdx.x * kBuildWaves + wave;
     if (g >= a.n_inst) return;
+    {   // feedback routing: an instance that has been given nothing since its table was built keeps it
+        const bool touched = a.pend_touched[g] != 0;
+        if (lane == 0 && touched) a.pend_touched[g] = 0;
+        if (a.only_touched && !touched) {
+            if (lane == 0) a.rank_acc[g] = 0;
+            return;
+        }
+    }
     int* ctx = reinterpret_cast<int*>(smem) + wave * 3 * kCap;  // this wave's contexts, by entry index
     int* olen = ctx + kCap;    // under a batch cap: length and context as given (ctx then holds them
     int* octx = olen + kCap;   // as they are when a newcomer would be admitted)
@@ -542,8 +552,8 @@ __global__ __launch_bounds__(kBlock) void k_ema(int n_inst, double w, const floa
 __global__ __launch_bounds__(kBlock) void k_commit(int64_t n, const int* __restrict__ inst,
                                                    const int* __restrict__ ctx0, const int* __restrict__ pred_len,
                                                    int* __restrict__ pend_cnt, int* __restrict__ pend_prompt,
-                                                   int* __restrict__ pend_len, int cap, int n_inst,
-                                                   int* __restrict__ counters)
+                                                   int* __restrict__ pend_len, int* __restrict__ pend_touched,
+                                                   int cap, int n_inst, int* __restrict__ counters)
 {
     const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const int lane = lane_id();
@@ -557,7 +567,10 @@ __global__ __launch_bounds__(kBlock) void k_commit(int64_t n, const int* __restr
         const int gl = __builtin_amdgcn_readlane(g, leader);
         const unsigned long long same = __ballot(act && g == gl);
         int base = 0;
-        if (lane == leader) base = atomicAdd(&pend_cnt[gl], __popcll(same));
+        if (lane == leader) {
+            base = atomicAdd(&pend_cnt[gl], __popcll(same));
+            pend_touched[gl] = 1;
+        }
         base = __builtin_amdgcn_readlane(base, leader);
         if (act && g == gl) slot = base + __popcll(same & ((1ull << lane) - 1ull));
         todo &= ~same;
@@ -587,7 +600,7 @@ int launch_commit(gr_fleet* f, int64_t n, const int* inst, const int* ctx0, cons
 {
     if (n == 0) return GR_OK;
     hipLaunchKernelGGL(k_commit, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, n, inst, ctx0, pred_len,
-                       f->pend_cnt, f->pend_prompt, f->pend_len, f->cap, f->n_inst, f->counters);
+                       f->pend_cnt, f->pend_prompt, f->pend_len, f->pend_touched, f->cap, f->n_inst, f->counters);
     return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
 }
 
@@ -616,6 +629,7 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
     b.n_inst = f->n_inst; b.max_entries = f->max_entries; b.max_len = f->max_len;
     b.pend_cnt = f->pend_cnt; b.pend_prompt = f->pend_prompt; b.pend_len = f->pend_len;
     b.use_pending = in.use_pending;
+    b.pend_touched = f->pend_touched; b.only_touched = in.use_pending && in.only_touched;
     b.batch_cap = f->has_cap ? f->batch_cap : nullptr;
     b.lam = f->lam; b.emaQ = f->emaQ; b.emaP = f->emaP; b.emaD = f->emaD;
     const int M = f->n_inst;
@@ -644,6 +658,7 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
     if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
     f->has_status = true;
     f->lam_built = f->lam;
+    f->tables_current = true;
     if (!in.use_pending) f->last_in = in;     // what a later feedback routing rebuilds from
     return GR_OK;
 }

@@ -119,12 +119,21 @@ def max_len_of(fl) -> int:
     return int(fl.max_len) if hasattr(fl, "max_len") else int(fl.spec.max_len)
 
 
+# How the handles of the checks below score a batch: None = the library's own choice (small
+# batches pair by pair, large ones grouped by length), 0 = always grouped.  tests/conftest.py
+# runs the GPU tests of the edge cases once each way.
+SMALL_BATCH_PAIRS: Optional[int] = None
+
+
 def make_handle(fl, max_requests: Optional[int] = None, max_entries: Optional[int] = None):
     me = int(max(np.diff(fl.act_off) + np.diff(fl.q_off)))
-    return binding.Fleet(fl.coef["delta"], fl.coef["alpha"], fl.coef["beta"], fl.coef["gamma"],
-                         fl.inst_class, max(me, 1) if max_entries is None else max_entries,
-                         max_len_of(fl),
-                         max(len(fl.in_prompt), 1) if max_requests is None else max_requests)
+    h = binding.Fleet(fl.coef["delta"], fl.coef["alpha"], fl.coef["beta"], fl.coef["gamma"],
+                      fl.inst_class, max(me, 1) if max_entries is None else max_entries,
+                      max_len_of(fl),
+                      max(len(fl.in_prompt), 1) if max_requests is None else max_requests)
+    if SMALL_BATCH_PAIRS is not None:
+        h.gr_set_small_batch_pairs(SMALL_BATCH_PAIRS)
+    return h
 
 
 def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit: int = 1 << 25,

@@ -12,6 +12,16 @@ from tests import parity
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(autouse=True, params=["auto", "grouped"])
+def scoring_layout(request):
+    """Every test here runs twice: with the library choosing how a batch is scored
+    (few pairs: a thread per pair; many: grouped by length), and always grouped."""
+    parity.SMALL_BATCH_PAIRS = None if request.param == "auto" else 0
+    yield
+    parity.SMALL_BATCH_PAIRS = None
+
+
 CLASSES = [(2e-5, 0.012, 2e-4, 2e-8), (5e-5, 0.025, 4e-4, 5e-8), (1.2e-4, 0.05, 8e-4, 1e-7)]
 
 

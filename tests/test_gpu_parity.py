@@ -9,6 +9,16 @@ from tests import parity
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["auto", "grouped"])
+def scoring_layout(request):
+    """Every test here runs twice: with the library choosing how a batch is scored
+    (few pairs: a thread per pair; many: grouped by length), and always grouped."""
+    parity.SMALL_BATCH_PAIRS = None if request.param == "auto" else 0
+    yield
+    parity.SMALL_BATCH_PAIRS = None
+
+
+
 def report(name, rep):
     print(f"\n[{name}] " + " ".join(f"{k}={v}" for k, v in rep.items()), flush=True)
 
