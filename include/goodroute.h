@@ -183,7 +183,10 @@ int gr_score_route_cached(gr_fleet* f, int64_t n_req,
  * and must still be valid and unchanged.  An instance takes routed requests
  * while it holds fewer than max_entries_per_inst entries; beyond that the
  * request is still reported but no longer counted (GR_DEV_ENTRIES_DROPPED).
- * Cost: one status rebuild and one scoring pass per chunk.
+ * Cost: one scoring pass and one status rebuild per chunk; the rebuild leaves
+ * instances that were given nothing in the chunk as they are (unless the blend
+ * weight, the observations or the caps have changed since the tables were built:
+ * then the first rebuild of the call takes every instance).
  *
  *   chunk      requests per decision round, >= 1 (cut to max_requests)
  * Other arguments as gr_score_route (no out_T).
