@@ -3,17 +3,21 @@
 //
 // T(r,g) = E_g(L_r) + c0_r * kappa_g(L_r) (see common.h), and E, kappa depend on
 // the request only through its length.  So a batch is first grouped by length
-// (a counting sort over the lengths present), E and kappa are looked up once per
-// (distinct length, instance) by binary search in the instance's sorted
-// lengths, and every (request, instance) pair then costs one multiply-add, the
-// feasibility compare and the running selections of Alg. 1.
+// (a counting sort over the lengths present), E is tabulated once per (distinct
+// length, instance) from the instance's sorted lengths (by counting: the
+// lengths of the batch are sorted too), and every (request, instance) pair then
+// costs one multiply-add and half a three-way minimum.
 //
-// Instances are visited in capability order (largest d_g first), 64 per wave
-// step, one per lane; the requests of a tile are wave-uniform scalars.  The
-// just-enough choice (feasible instance of largest d_g) is then the first set
-// bit of the feasibility ballot of the first block that has one; the fallback
-// (smallest T) is a per-lane running minimum reduced across the wave at the end.
-#include <cfloat>
+// Instances sit in capability order (largest d_g first), 64 per wave step, one
+// per lane; the requests of a tile are wave-uniform scalars.  A pair only
+// enters its request's running minimum per lane: Alg. 1's feasible set is
+// non-empty exactly when the least latency meets the deadline, the just-enough
+// choice (feasible instance of largest d_g) is then the first feasible position
+// in capability order, found with bounds over runs of 16 positions, and the
+// fallback (smallest T) is the position of the minimum.
+//
+// A batch of a few requests skips grouping and table: a thread per pair with
+// its own binary search (k_direct).
 
 #include "common.h"
 
@@ -866,8 +870,8 @@ constexpr int kDenseBlocks = 2;      // blocks looked at for all requests at onc
 // request's running minimum per lane (one three-way minimum per two pairs).
 // Alg. 1's feasible set is non-empty exactly when that minimum is <= D, so the
 // feasibility test of every pair is implied; only requests that have a
-// feasible instance are walked again, in capability order, up to their first
-// one (the just-enough choice).  The others take the instance of the minimum,
+// feasible instance are looked at again, for their first one in capability
+// order (the just-enough choice).  The others take the instance of the minimum,
 // found by recomputing the positions of the lane that holds it (the earliest
 // position in capability order among equal minima).
 //
