@@ -18,6 +18,7 @@
 //
 // A batch of a few requests skips grouping and table: a thread per pair with
 // its own binary search (k_direct).
+#include <cfloat>
 
 #include "common.h"
 
