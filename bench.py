@@ -51,7 +51,7 @@ TILE_MIGRATE_HEAVY_TRAFFIC_BYTES = int((186.7 + 177.3) * 2**20)   # fetch + writ
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--blend", type=float, default=0.0,
                     help="weight of the black-box status (Sec. 3.3) after three rounds of synthetic observations")
     ap.add_argument("--batch-cap", action="store_true", help="per-instance caps on the decode batch (Sec. 3.1)")
@@ -59,7 +59,7 @@ def parse():
                     help="route the incoming batch with the status refreshed every so many requests")
     ap.add_argument("--latency-iters", type=int, default=100,
                     help="calls of gr_score_route timed one by one for the route-batch latency")
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="heavy", help="tiny | mid | large | migrate | heavy")
     ap.add_argument("--prefixes", type=float, default=0.0,
                     help="mean number of cached prefixes per incoming request (Eq. 2's H); 0: none")
