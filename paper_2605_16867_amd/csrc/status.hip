@@ -134,8 +134,10 @@ constexpr int kBuildWaves = kBlock / kWave;
 
 constexpr int log2_of(int v) { return v <= 1 ? 0 : 1 + log2_of(v / 2); }
 
+// (up to 8 sort words per lane the kernel is held to 128 registers, four waves per SIMD: a fleet
+// of 4 096 instances is then resident at once)
 template <int kEPL, bool kCapAware>
-__global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
+__global__ __launch_bounds__(kBlock, (kEPL <= 8 && !kCapAware ? 4 : 1)) void k_build(BuildArgs a)
 {
     extern __shared__ uint32_t smem[];
     constexpr int kCap = kWave * kEPL;
@@ -171,7 +173,21 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
     const int* pp = a.pend_prompt + (size_t)g * kCap;
     const int* pl = a.pend_len + (size_t)g * kCap;
 
-    // load, entry i = 64 r + lane: one sort word per entry = (remaining length << kIdxBits) | i
+    // load, entry i = 64 r + lane.  First every entry's three words, from wherever its kind keeps
+    // them (running, queued, routed since the status), so that all loads are in flight together;
+    // then one sort word per entry = (remaining length << kIdxBits) | i.
+    int rem_in[kEPL], c_in[kEPL], gen_in[kEPL];
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) {
+        const int i = r * kWave + lane;
+        const int* p_rem = a.act_rem + a0 + i;
+        const int* p_ctx = a.act_prompt + a0 + i;
+        if (i >= A + Q) { p_rem = pl + (i - A - Q); p_ctx = pp + (i - A - Q); }
+        else if (i >= A) { p_rem = a.q_len + q0 + (i - A); p_ctx = a.q_prompt + q0 + (i - A); }
+        rem_in[r] = i < N ? *p_rem : 0;
+        c_in[r] = i < N ? *p_ctx : 0;
+        gen_in[r] = i < A ? a.act_gen[a0 + i] : 0;
+    }
     uint32_t key[kEPL];
     long long qsum = 0;
 #pragma unroll
@@ -179,26 +195,19 @@ __global__ __launch_bounds__(kBlock) void k_build(BuildArgs a)
         const int i = r * kWave + lane;
         uint32_t word = 0xFFFFFFFFu;        // past the last entry: sorts to the end
         if (i < N) {
-            int rem, c;
-            if (i < A) {
-                rem = a.act_rem[a0 + i];
-                c = a.act_prompt[a0 + i] + a.act_gen[a0 + i];
-                a.act_inst[a0 + i] = g;
-            } else if (i < A + Q) {
-                rem = a.q_len[q0 + i - A];
-                c = a.q_prompt[q0 + i - A];
-                qsum += c;
-            } else {
-                rem = pl[i - A - Q];
-                c = pp[i - A - Q];
-                qsum += c;
-            }
+            int rem = rem_in[r];
+            const int c = c_in[r] + gen_in[r];
+            if (i >= A) qsum += c;
             if (rem < 0 || rem > a.max_len) { rem = min(max(rem, 0), a.max_len); status |= GR_DEV_LEN_CLAMPED; }
             word = ((uint32_t)rem << kIdxBits) | (uint32_t)i;
             ctx[i] = c;
         }
         key[r] = word;
     }
+    // (stores on their own: a store between two uses of loaded words would make the second wait for it)
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r)
+        if (r * kWave + lane < A) a.act_inst[a0 + r * kWave + lane] = g;
     if (status) atomicOr(&a.counters[0], status);
     if (Q + P > 0) qsum = wave_sum(qsum);   // Q and P are the same in every lane
     double q = cc.delta * (double)qsum;
