@@ -306,9 +306,24 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
         }
     }
 
+    // the lengths of a pass's rows are fetched one pass ahead: every workgroup reads them from L2,
+    // and that latency would otherwise sit in the middle of every pass
+    int Lnext[kPerLane];
+#pragma unroll
+    for (int i = 0; i < kPerLane; ++i) {
+        const int u = ub + lane + kWave * i;
+        Lnext[i] = u < ue ? a.row_len[u] : 0;
+    }
     int buf = 0;
     for (int u0 = ub; u0 < ue; u0 += kMemoU, buf ^= 1) {
         float* tile = tiles + buf * kMemoTile;
+        int Lrow[kPerLane];
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            Lrow[i] = Lnext[i];
+            const int u = u0 + kMemoU + lane + kWave * i;
+            Lnext[i] = u < ue ? a.row_len[u] : 0;
+        }
         if (g >= 0) {
             reinterpret_cast<int4*>(cnt)[lane] = make_int4(0, 0, 0, 0);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -338,12 +353,11 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
             for (int i = 0; i < kPerLane; ++i) {
-                const int row = lane + kWave * i, u = u0 + row;
+                const int row = lane + kWave * i;
                 const int k = cnt[row];
-                const int L = u < U ? a.row_len[u] : 0;
                 float2 gh = head;
                 if (k > 0) gh = GH[k - 1];
-                const float Lf = (float)L;
+                const float Lf = (float)Lrow[i];
                 const float tri = Lf * (Lf - 1.0f) * 0.5f;
                 tile[row * (kMemoP + 1) + pi] = fmaf(Lf, gh.y, gh.x) + tri * (gam * (float)(N - k + 1));
             }
