@@ -932,14 +932,19 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
         lo = nlo;
     }
     const int u = lo;
-    const int r0 = a.row_off[u] + (t - a.tile_off[u]) * kTileReq;
-    const int nreq = min(kTileReq, a.row_off[u + 1] - r0);
+    // The row's requests are dealt out to its tiles in turn (request q of the row goes to tile
+    // q mod tiles), not in runs of 32: neighbours in grouped order tend to come from one instance,
+    // and requests whose answer lands on their own (excluded) instance are redone one by one, which
+    // would otherwise pile up in single tiles.
+    const int row_begin = a.row_off[u], row_n = a.row_off[u + 1] - row_begin;
+    const int row_tiles = a.tile_off[u + 1] - a.tile_off[u], tl = t - a.tile_off[u];
+    const int nreq = (row_n - tl + row_tiles - 1) / row_tiles;       // requests q = tl, tl + tiles, ..
 
     // lanes past the tile's last request carry a dummy that is never feasible and never reported
     ReqRec rec;
     rec.c0 = 0.f; rec.D = -__builtin_inff(); rec.pex = -1; rec.orig = -1;
     const bool mine = lane < nreq;
-    if (mine) rec = a.recs[r0 + lane];
+    if (mine) rec = a.recs[row_begin + tl + lane * row_tiles];
     // padded positions hold T = +inf and must stay infeasible even for D = +inf; a NaN budget is never met
     const float Dc = rec.D > FLT_MAX ? FLT_MAX : rec.D;
 
