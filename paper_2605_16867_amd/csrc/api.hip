@@ -92,6 +92,7 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         dev_alloc(&f->row_len, f->row_cap) && dev_alloc(&f->row_off, f->row_cap + 1) &&
         dev_alloc(&f->tile_off, f->row_cap + 1) && dev_alloc(&f->len_row, f->bins) && dev_alloc(&f->len_ceil, f->bins) && dev_alloc(&f->totals, 4) &&
         dev_alloc(&f->recs, f->req_cap) && dev_alloc(&f->memo, (size_t)f->row_cap * f->m_pad) &&
+        dev_alloc(&f->tile_row, (size_t)(f->req_cap / kTileReq + f->row_cap + 1)) &&
         dev_alloc(&f->grp_min, (size_t)f->row_cap * (f->m_pad / kMemoP)) && dev_alloc(&f->grp_k, f->m_pad / kMemoP) &&
         dev_alloc(&f->direct_best, 2 * (size_t)kDirectMax);
     if (!ok) { gr_destroy(f); return GR_ERR_NOMEM; }
@@ -125,7 +126,7 @@ int gr_destroy(gr_fleet* f)
     void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabGH, f->headGH, f->hN, f->hD, f->emaQ, f->emaP, f->emaD, f->rank_acc,
                     f->rank, f->order, f->posK, f->act_inst, f->pend_cnt, f->pend_touched, f->pend_prompt, f->pend_len,
                     f->scratch_finish, f->batch_cap, f->counters, f->len_cnt, f->len_base, f->row_len,
-                    f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, f->recs, f->memo, f->grp_min, f->grp_k, f->direct_best};
+                    f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, f->recs, f->memo, f->tile_row, f->grp_min, f->grp_k, f->direct_best};
     int rc = GR_OK;
     for (void* p : ptrs)
         if (p && hipFree(p) != hipSuccess) rc = GR_ERR_HIP;

@@ -155,6 +155,7 @@ struct gr_fleet {
     int* totals = nullptr;    // [4] requests, distinct lengths, tiles
     gr::ReqRec* recs = nullptr;  // [req_cap] requests in grouped order
     float* memo = nullptr;       // [row_cap][m_pad] E per distinct length and position
+    int* tile_row = nullptr;     // [req_cap / kTileReq + row_cap + 1] the row of every tile
     float* grp_min = nullptr;    // [m_pad / kMemoP][row_cap] least E of each run of kMemoP positions, per row
     float2* grp_k = nullptr;     // [m_pad / kMemoP] least delta and least gamma of each run
     bool tables_current = false;   // every instance's table is from the last inputs, blend weight and caps

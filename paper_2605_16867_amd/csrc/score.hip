@@ -229,6 +229,8 @@ struct MemoArgs {
     float* grp_min;        // [m_pad / kMemoP][row_cap]
     float2* grp_k;         // [m_pad / kMemoP]
     const float2* posK;
+    const int* tile_off;   // [rows + 1] first tile of each row
+    int* tile_row;         // [tiles] the row of each tile (written here, for the scoring kernel)
     int n_inst, m_pad, cap, row_cap;
     float keep;      // 1 - weight of the black-box estimate: scales the white-box curvature gamma
 };
@@ -317,6 +319,14 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
     int buf = 0;
     for (int u0 = ub; u0 < ue; u0 += kMemoU, buf ^= 1) {
         float* tile = tiles + buf * kMemoTile;
+        // the row of every tile, for the scoring kernel: the pass's rows are shared out over the
+        // workgroups of this run of rows and their waves (usually one row per workgroup and pass)
+        for (int r = blockIdx.x + gridDim.x * pi; r < kMemoU; r += gridDim.x * kMemoP) {
+            const int u = u0 + r;
+            if (u >= ue) break;
+            const int t0 = a.tile_off[u], t1 = a.tile_off[u + 1];
+            for (int t = t0 + lane; t < t1; t += kWave) a.tile_row[t] = u;
+        }
         int Lrow[kPerLane];
 #pragma unroll
         for (int i = 0; i < kPerLane; ++i) {
@@ -403,6 +413,7 @@ struct TileArgs {
     const float2* posK;    // [m_pad] (delta, gamma) of the instance at each position
     const float* grp_min;  // [m_pad / kMemoP][row_cap] least E of each run of kMemoP positions
     const float2* grp_k;   // [m_pad / kMemoP] least delta and gamma of each run
+    const int* tile_row;   // [tiles] the row of each tile
     int row_cap;
     int* out_inst;
     float* out_slack;
@@ -920,18 +931,7 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     }
     if (t >= NT) return;
 
-    // row of this tile: the last u with tile_off[u] <= t, by a 64-way search
-    int lo = 0, len = U;
-    while (len > 1) {
-        const int stride = (len + kWave - 1) / kWave;
-        const int idx = lo + lane * stride;
-        const bool le = idx < lo + len && a.tile_off[idx] <= t;
-        const int cnt = __popcll(__ballot(le));
-        const int nlo = lo + (cnt - 1) * stride;
-        len = min(stride, lo + len - nlo);
-        lo = nlo;
-    }
-    const int u = lo;
+    const int u = a.tile_row[t];        // (written by the memo kernel)
     // The row's requests are dealt out to its tiles in turn (request q of the row goes to tile
     // q mod tiles), not in runs of 32: neighbours in grouped order tend to come from one instance,
     // and requests whose answer lands on their own (excluded) instance are redone one by one, which
@@ -1332,7 +1332,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         MemoArgs m{};
         m.totals = f->totals; m.row_len = f->row_len; m.len_ceil = f->len_ceil; m.order = f->order; m.hN = f->hN;
         m.cls = f->cls; m.inst_class = f->inst_class;
-        m.tabR = f->tabR; m.tabGH = f->tabGH; m.headGH = f->headGH; m.memo = f->memo; m.grp_min = f->grp_min; m.grp_k = f->grp_k; m.posK = f->posK; m.row_cap = (int)f->row_cap;
+        m.tabR = f->tabR; m.tabGH = f->tabGH; m.headGH = f->headGH; m.memo = f->memo; m.grp_min = f->grp_min; m.grp_k = f->grp_k; m.posK = f->posK; m.tile_off = f->tile_off; m.tile_row = f->tile_row; m.row_cap = (int)f->row_cap;
         m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.cap = f->cap; m.keep = (float)(1.0 - f->lam_built);
         // every workgroup walks all lengths; with few instances the lengths are dealt out to several
         const int gx = f->m_pad / kMemoP;
@@ -1345,7 +1345,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     {
         TileArgs t{};
         t.totals = f->totals; t.row_len = f->row_len; t.row_off = f->row_off; t.tile_off = f->tile_off;
-        t.order = f->order; t.recs = f->recs; t.memo = f->memo; t.posK = f->posK; t.grp_min = f->grp_min; t.grp_k = f->grp_k; t.row_cap = (int)f->row_cap;
+        t.order = f->order; t.recs = f->recs; t.memo = f->memo; t.posK = f->posK; t.grp_min = f->grp_min; t.grp_k = f->grp_k; t.tile_row = f->tile_row; t.row_cap = (int)f->row_cap;
         t.out_inst = out.inst; t.out_slack = out.slack; t.out_fallback = out.fallback; t.out_T = out.T;
         t.n_inst = f->n_inst; t.m_pad = f->m_pad;
         const int64_t max_tiles = (n + kTileReq - 1) / kTileReq + max_rows;
