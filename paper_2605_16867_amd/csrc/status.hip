@@ -83,43 +83,62 @@ __device__ __forceinline__ void order2(uint32_t& lo, uint32_t& hi)
 }
 
 // Ascending bitonic sort of 64 * kEPL words, word v = lane * kEPL + r in key[r].
-// Stage k merges sorted runs of k/2 into runs of k: first v against its mirror
-// image v ^ (k-1) in the run, then distances k/4, k/8, .. 1; the lower position
-// always keeps the smaller word.
+// Level K merges sorted runs of K/2 into runs of K: first v against its mirror
+// image v ^ (K-1) in the run, then distances K/4, K/8, .. 1; the lower position
+// always keeps the smaller word.  Levels and distances are template parameters
+// (the network is straight-line code with every register named at compile
+// time; as loops over K and the distance the larger sizes were left rolled,
+// with registers addressed indirectly).
+template <int kEPL, int K>
+__device__ __forceinline__ void bitonic_mirror(uint32_t (&key)[kEPL], int lane, int lane4)
+{
+    if constexpr (K <= kEPL) {
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r)
+            if (r < (r ^ (K - 1))) order2(key[r], key[r ^ (K - 1)]);
+    } else {
+        constexpr int lm = K / kEPL - 1;
+        const uint32_t bound = (lane & (K / kEPL / 2)) ? 0xFFFFFFFFu : 0u;   // upper partner keeps the larger
+        uint32_t p[kEPL];
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r) p[r] = fetch_xor(key[kEPL - 1 - r], lm, lane4);
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r) key[r] = med3_u32(key[r], p[r], bound);
+    }
+}
+
+template <int kEPL, int J>
+__device__ __forceinline__ void bitonic_distances(uint32_t (&key)[kEPL], int lane, int lane4)
+{
+    if constexpr (J >= 1) {
+        if constexpr (J < kEPL) {
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r)
+                if ((r & J) == 0) order2(key[r], key[r | J]);
+        } else {
+            constexpr int lm = J / kEPL;
+            const uint32_t bound = (lane & lm) ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r) key[r] = med3_u32(key[r], fetch_xor(key[r], lm, lane4), bound);
+        }
+        bitonic_distances<kEPL, J / 2>(key, lane, lane4);
+    }
+}
+
+template <int kEPL, int K>
+__device__ __forceinline__ void bitonic_levels(uint32_t (&key)[kEPL], int lane, int lane4)
+{
+    if constexpr (K <= kWave * kEPL) {
+        bitonic_mirror<kEPL, K>(key, lane, lane4);
+        bitonic_distances<kEPL, K / 4>(key, lane, lane4);
+        bitonic_levels<kEPL, 2 * K>(key, lane, lane4);
+    }
+}
+
 template <int kEPL>
 __device__ __forceinline__ void bitonic_sort(uint32_t (&key)[kEPL], int lane)
 {
-    const int lane4 = lane << 2;
-    constexpr int kCap = kWave * kEPL;
-#pragma unroll
-    for (int k = 2; k <= kCap; k <<= 1) {
-        if (k <= kEPL) {
-#pragma unroll
-            for (int r = 0; r < kEPL; ++r)
-                if (r < (r ^ (k - 1))) order2(key[r], key[r ^ (k - 1)]);
-        } else {
-            const int lm = k / kEPL - 1;
-            const uint32_t bound = (lane & (k / kEPL / 2)) ? 0xFFFFFFFFu : 0u;   // upper partner keeps the larger
-            uint32_t p[kEPL];
-#pragma unroll
-            for (int r = 0; r < kEPL; ++r) p[r] = fetch_xor(key[kEPL - 1 - r], lm, lane4);
-#pragma unroll
-            for (int r = 0; r < kEPL; ++r) key[r] = med3_u32(key[r], p[r], bound);
-        }
-#pragma unroll
-        for (int j = k / 4; j >= 1; j >>= 1) {
-            if (j < kEPL) {
-#pragma unroll
-                for (int r = 0; r < kEPL; ++r)
-                    if ((r & j) == 0) order2(key[r], key[r | j]);
-            } else {
-                const int lm = j / kEPL;
-                const uint32_t bound = (lane & lm) ? 0xFFFFFFFFu : 0u;
-#pragma unroll
-                for (int r = 0; r < kEPL; ++r) key[r] = med3_u32(key[r], fetch_xor(key[r], lm, lane4), bound);
-            }
-        }
-    }
+    bitonic_levels<kEPL, 2>(key, lane, lane << 2);
 }
 
 // Exclusive prefix over the lanes of a wave, and the total.
