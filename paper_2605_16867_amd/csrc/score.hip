@@ -888,6 +888,8 @@ __device__ __forceinline__ void main_pass(const RowView& rv, const float (&c0)[k
 constexpr int kSparseFeasible = 8;   // up to this many feasible requests of a tile go one by one
 constexpr int kDenseBlocks = 2;      // blocks looked at for all requests at once before the bounded walk
 
+constexpr int kXcdRun = 8;     // workgroups in a row that stay on one XCD
+
 // One wave per tile: up to kTileReq requests of one length against all
 // instances.  Lane = position in capability order within a block of 64; the
 // requests' prefill lengths are wave-uniform scalars.
@@ -917,11 +919,13 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int NT = a.totals[2], U = a.totals[1];
-    // consecutive tiles share a table row: keep them on one XCD (workgroups go round-robin over
-    // 8), each XCD taking an equal run of the workgroups that have tiles at all
-    const int per_xcd = ((NT + kW - 1) / kW + 7) >> 3;
-    if ((int)(blockIdx.x >> 3) >= per_xcd) return;
-    const int bid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    // consecutive tiles share a table row: keep them on one XCD (workgroups go round-robin over 8)
+    // in runs of kXcdRun workgroups' worth of tiles, dealt to the XCDs in turn: tiles get cheaper
+    // towards the long lengths (few requests each), and equal eighths of the tiles are not equal work
+    const int groups = (NT + kW - 1) / kW;
+    const int seq = blockIdx.x >> 3;
+    const int bid = (seq / kXcdRun) * (8 * kXcdRun) + (int)(blockIdx.x & 7) * kXcdRun + seq % kXcdRun;
+    if (bid >= groups) return;
     const int t = bid * kW + wave;
     float2* lds_grpK = lds_posK + a.m_pad;      // least (delta, gamma) of each run of kMemoP positions
     if (kLdsK) {
@@ -1354,7 +1358,7 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         const size_t k_bytes = (size_t)(f->m_pad + f->m_pad / kMemoP) * sizeof(float2);
         const int kw = k_bytes <= 49152 ? 8 : k_bytes <= 65536 ? 12 : 4;
         unsigned blocks = (unsigned)((max_tiles + kw - 1) / kw);
-        blocks = (blocks + 7u) & ~7u;
+        blocks = (blocks + 8u * kXcdRun - 1) / (8u * kXcdRun) * (8u * kXcdRun);
         ProfScope ps(f, kTileRoute + off, s);
 #define GR_LAUNCH_TILE(W, L) \
         if (out.T) hipLaunchKernelGGL((k_tile<true, W>), dim3(blocks), dim3(W * kWave), L, s, t); \
