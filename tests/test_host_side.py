@@ -28,6 +28,20 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, n) is not None
 
 
+def test_a_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """The binding has no other implementation to fall back on: without the
+    built library every entry point is unavailable, loudly."""
+    import pytest
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libgoodroute.so"))
+    with pytest.raises(ImportError):
+        binding.lib()
+    with pytest.raises(ImportError):
+        binding.Fleet([1e-5], [0.01], [1e-4], [1e-8], [0], 8, 100, 8)
+    src = open(os.path.join(ROOT, "paper_2605_16867_amd", "binding.py")).read()
+    assert "oracle" not in src          # the binding never reaches for the CPU reference
+
+
 def test_strerror_needs_no_gpu():
     assert binding.strerror(0) == "ok"
     assert "invalid" in binding.strerror(-1)
