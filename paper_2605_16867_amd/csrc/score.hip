@@ -969,12 +969,18 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
         minT[j] = __builtin_inff();
     }
 
-    // ---- main pass over the requests the tile really has, in eights (most lengths of a batch
+    // ---- main pass over the requests the tile really has, in fours (most lengths of a batch
     // have only a few requests, and a tile is one length's)
-    if (nreq <= 8) main_pass<8>(rv, c0, minT, lane);
-    else if (nreq <= 16) main_pass<16>(rv, c0, minT, lane);
-    else if (nreq <= 24) main_pass<24>(rv, c0, minT, lane);
-    else main_pass<32>(rv, c0, minT, lane);
+    switch ((nreq + 3) >> 2) {
+        case 1: main_pass<4>(rv, c0, minT, lane); break;
+        case 2: main_pass<8>(rv, c0, minT, lane); break;
+        case 3: main_pass<12>(rv, c0, minT, lane); break;
+        case 4: main_pass<16>(rv, c0, minT, lane); break;
+        case 5: main_pass<20>(rv, c0, minT, lane); break;
+        case 6: main_pass<24>(rv, c0, minT, lane); break;
+        case 7: main_pass<28>(rv, c0, minT, lane); break;
+        default: main_pass<32>(rv, c0, minT, lane); break;
+    }
 
     // ---- per request: the least latency and the lane that holds it (lane j keeps request j's)
     float Tm = __builtin_inff();
