@@ -45,7 +45,7 @@ SCAN_EXTRA_BYTES_PER_ENTRY = 5.0
 # HBM bytes per launch of the dominant kernel (k_tile, migration launch of the "heavy" fleet) from
 # the rocprofv3 counter passes summarised under profiles/, scaled by the plain-copy calibration;
 # None whenever that kernel has changed since the counters were taken.
-TILE_MIGRATE_HEAVY_TRAFFIC_BYTES = int((210.4 + 200.4) * 2**20)   # fetch + write MiB per launch
+TILE_MIGRATE_HEAVY_TRAFFIC_BYTES = int((210.6 + 200.4) * 2**20)   # fetch + write MiB per launch
 
 
 def parse():
@@ -189,10 +189,19 @@ def main():
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
-    # timed region: HIP events around the launches of the kernels whose roofline is reported
-    # (scoring tiles, status build); an event pair around each of the dozen short kernels as well
-    # would cost about a tenth of the step
-    h.gr_profile_select(["k_tile", "k_build"])
+    # before the timed region: the same steps with every kernel timed, for the breakdown and to
+    # find the kernel the step spends most of its time in
+    h.gr_profile_select(None)
+    h.gr_profile_enable(prof_slots * a.steps)
+    for _ in range(a.steps):
+        step()
+    torch.cuda.synchronize()
+    prof_all = h.gr_profile_read()
+    heaviest = max((n for n in prof_all if n.startswith(("k_tile", "k_build")) and prof_all[n][1]),
+                   key=lambda n: prof_all[n][0])
+    # timed region: HIP events around the launches of that kernel only (an event pair costs a few
+    # microseconds of stream time: around each of the dozen launches of a step, about a tenth of it)
+    h.gr_profile_select([heaviest])
     h.gr_profile_enable(prof_slots * a.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -201,13 +210,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     prof = h.gr_profile_read()
-    # outside the timed region: the same steps with every kernel timed, for the breakdown
     h.gr_profile_select(None)
-    h.gr_profile_enable(prof_slots * a.steps)
-    for _ in range(a.steps):
-        step()
-    torch.cuda.synchronize()
-    prof_all = h.gr_profile_read()
     h.gr_profile_enable(0)
     for name, v in prof_all.items():
         if not prof.get(name, (0.0, 0))[1]:
