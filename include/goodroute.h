@@ -34,6 +34,14 @@
  * gr_create; no call after gr_create allocates.  Calls on one handle must not
  * overlap.  Token counts are int32; times are seconds.
  *
+ * The calls that take a stream only launch kernels on it (no copy, no memset,
+ * no synchronisation), so a sequence of them can be recorded into a HIP graph
+ * and replayed on the same buffers.  What the host decides at call time is
+ * recorded with it: sizes, the blend weight and caps in force, and how a
+ * batch is scored (gr_set_small_batch_pairs).  gr_create, gr_destroy, the
+ * gr_set_* calls, gr_profile_* and gr_device_status copy or synchronise and
+ * are not for use inside a capture.
+ *
  * Input contract for device data (not validated on the host): remaining and
  * predicted lengths in [1, max_len]; prompt >= 1; generated >= 0; entries per
  * instance <= max_entries_per_inst; CSR offsets non-decreasing, starting at 0.
