@@ -1037,16 +1037,24 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     const int src = lane & (kTileReq - 1);
     const float s_c0 = __shfl(rec.c0, src, kWave), s_Tm = __shfl(Tm, src, kWave);
     const int s_win = __shfl(win, src, kWave);
+    // The block is tracked as a float key, T - min scaled up plus the block number: the key is the
+    // block number exactly where T equals the minimum (the difference of two floats is zero only
+    // if they are equal, and T >= min) and huge elsewhere; the least key is the earliest such block.
+    // That is three instructions of the class that issues two per slot and half a three-way
+    // minimum per block, instead of a compare and a select.
     int firstB = 0x7fffffff;
     if (__ballot(mine && foundP < 0)) {
         const int lw = s_win & (kWave - 1), half = lane >> 5;
         const float* __restrict__ pe = rv.E + half * kWave + lw;
         const float2* __restrict__ pk = rv.posK + half * kWave + lw;
+        float blk = (float)half, key = 0x1p100f;
 #pragma unroll 8
         for (int i = 0; i < rv.nblk / 2; ++i) {       // block 2 i + half
             const float Tc = fmaf(s_c0, kappa_of(pk[i * 2 * kWave], rv.Lf), pe[i * 2 * kWave]);
-            firstB = Tc == s_Tm ? min(firstB, 2 * i + half) : firstB;
+            key = fminf(key, fmaf(Tc - s_Tm, 0x1p100f, blk));
+            blk += 2.0f;
         }
+        if (key < 0x1p30f) firstB = (int)key;
     }
     firstB = min(firstB, __shfl_xor(firstB, 32, kWave));
     const int candP = firstB < rv.nblk ? firstB * kWave + (win & (kWave - 1)) : -1;
