@@ -864,13 +864,24 @@ __device__ __forceinline__ void main_pass(const RowView& rv, const float (&c0)[k
                                           float (&minT)[kTileReq], int lane)
 {
     struct Step { float Ea, Eb; float2 Ka, Kb; };
-    // block starts are wave-uniform (scalar address arithmetic), the lane adds a fixed offset
-    const unsigned ul = (unsigned)lane;
+    // Block starts are wave-uniform.  The table row is read through a buffer descriptor: the
+    // address is base + the lane's fixed byte offset + a scalar offset that the scalar unit
+    // advances, so a read costs no vector arithmetic (with a plain pointer the compiler folds the
+    // lane's offset into a loop-invariant 64-bit vector base and adds the block offset to it with
+    // a shift-and-add per step, an instruction of the one-per-slot class).  The coefficient pairs
+    // are at the lane's own address plus a scalar offset: a plain add.
+    const int lane_e = lane * (int)sizeof(float);
+    const __amdgpu_buffer_rsrc_t row = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(rv.E), 0, rv.nblk * kWave * (int)sizeof(float), 0x00020000 /* 32-bit elements */);
+    const char* const k_lane = reinterpret_cast<const char*>(rv.posK + (unsigned)lane);
     auto fetch = [&](Step& st, int b) {
-        const float* __restrict__ eb = rv.E + (unsigned)b * kWave;
-        const float2* __restrict__ kb = rv.posK + (unsigned)b * kWave;
-        st.Ea = eb[ul]; st.Eb = eb[kWave + ul];
-        st.Ka = kb[ul]; st.Kb = kb[kWave + ul];
+        const int e_off = b * (kWave * (int)sizeof(float));
+        unsigned k_off = (unsigned)b * (unsigned)(kWave * sizeof(float2));
+        asm volatile("" : "+s"(k_off));      // (a scalar, added as it is)
+        st.Ea = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(row, lane_e, e_off, 0));
+        st.Eb = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(row, lane_e + kWave * (int)sizeof(float), e_off, 0));
+        const float2* __restrict__ kb = reinterpret_cast<const float2*>(k_lane + k_off);
+        st.Ka = kb[0]; st.Kb = kb[kWave];
     };
     auto fold = [&](const Step& st) {
         const float ka = kappa_of(st.Ka, rv.Lf), kb = kappa_of(st.Kb, rv.Lf);
@@ -975,10 +986,14 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     rv.Lf = (float)a.row_len[u];
     rv.nblk = a.m_pad / kWave;
 
+    // the requests' prefill lengths as scalars: read again through the scalar cache (the lanes hold
+    // them too, but a read of a lane is a vector instruction of the one-per-slot class); slots past
+    // the tile's last request repeat the last one, their results are never used
     float c0[kTileReq], minT[kTileReq];
+    const ReqRec* __restrict__ tile_recs = a.recs + row_begin + tl;
 #pragma unroll
     for (int j = 0; j < kTileReq; ++j) {
-        c0[j] = readlane_f(rec.c0, j);
+        c0[j] = tile_recs[(size_t)min(j, nreq - 1) * row_tiles].c0;
         minT[j] = __builtin_inff();
     }
 
