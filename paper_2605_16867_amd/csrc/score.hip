@@ -968,14 +968,6 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     const int row_tiles = a.tile_off[u + 1] - a.tile_off[u], tl = t - a.tile_off[u];
     const int nreq = (row_n - tl + row_tiles - 1) / row_tiles;       // requests q = tl, tl + tiles, ..
 
-    // lanes past the tile's last request carry a dummy that is never feasible and never reported
-    ReqRec rec;
-    rec.c0 = 0.f; rec.D = -__builtin_inff(); rec.pex = -1; rec.orig = -1;
-    const bool mine = lane < nreq;
-    if (mine) rec = a.recs[row_begin + tl + lane * row_tiles];
-    // padded positions hold T = +inf and must stay infeasible even for D = +inf; a NaN budget is never met
-    const float Dc = rec.D > FLT_MAX ? FLT_MAX : rec.D;
-
     RowView rv;
     rv.E = a.memo + (size_t)u * a.m_pad;
     rv.grpE = a.grp_min + u;
@@ -1030,6 +1022,17 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
         if (nreq > 8) tile_minima4<8>(minT, Tm, win);
         if (nreq > 12) tile_minima4<12>(minT, Tm, win);
     }
+
+    // The lanes' own request records (lane j: request j) are only needed from here on: read after
+    // the main pass and the minima, they do not sit in registers (or scratch) through them.
+    // Lanes past the tile's last request carry a dummy that is never feasible and never reported.
+    __builtin_amdgcn_sched_barrier(0);
+    ReqRec rec;
+    rec.c0 = 0.f; rec.D = -__builtin_inff(); rec.pex = -1; rec.orig = -1;
+    const bool mine = lane < nreq;
+    if (mine) rec = tile_recs[(size_t)lane * row_tiles];
+    // padded positions hold T = +inf and must stay infeasible even for D = +inf; a NaN budget is never met
+    const float Dc = rec.D > FLT_MAX ? FLT_MAX : rec.D;
 
     // ---- requests with a feasible instance: the first one in capability order
     int foundP = -1;
