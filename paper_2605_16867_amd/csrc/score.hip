@@ -477,6 +477,19 @@ __device__ inline void writelane(int& dst, int uniform_value)
     asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(dst) : "s"(uniform_value), "n"(kLane));
 }
 
+// Put a wave-uniform value into the lane whose (wave-uniform) number is only
+// known at run time: the lane select travels in m0, the value in a scalar
+// register.
+__device__ inline void writelane_at(float& dst, float uniform_value, int uniform_lane)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0" : "+v"(dst) : "s"(uniform_value), "s"(uniform_lane) : "m0");
+}
+
+__device__ inline void writelane_at(int& dst, int uniform_value, int uniform_lane)
+{
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0" : "+v"(dst) : "s"(uniform_value), "s"(uniform_lane) : "m0");
+}
+
 // Requests kJ0 .. kJ0+3 of a tile: their least latency over the wave and the
 // lane that holds it (kWave when several lanes do), left in lanes kJ0 .. kJ0+3
 // of Tm and win.
@@ -672,7 +685,8 @@ __device__ inline void first_feasible_sparse(const RowView& rv, float rec_c0, fl
                 if (feas) {
                     const int fl = __ffsll((long long)feas) - 1;
                     const float Tf = readlane_f(T, fl);
-                    if (lane == j) { foundP = (b0 + i) * kWave + fl; foundT = Tf; }
+                    writelane_at(foundP, (b0 + i) * kWave + fl, j);
+                    writelane_at(foundT, Tf, j);
                     fm &= ~(1ull << j);
                 }
             }
@@ -722,7 +736,8 @@ __device__ inline unsigned long long first_feasible_dense(const RowView& rv, con
                     if (feas) {
                         const int fl = __ffsll((long long)feas) - 1;
                         const float Tf = readlane_f(T, fl);
-                        if (lane == j) { foundP = (b0 + i) * kWave + fl; foundT = Tf; }
+                        writelane_at(foundP, (b0 + i) * kWave + fl, j);
+                        writelane_at(foundT, Tf, j);
                         left &= ~(1u << j);
                         D[j] = -__builtin_inff();
                     }
@@ -764,15 +779,17 @@ __device__ inline void first_feasible_bounded(const RowView& rv, float rec_c0, f
         fm &= fm - 1;
         const float c0j = readlane_f(rec_c0, j), Dj = readlane_f(Dc, j);
         bool found = false;
-        // looks at the 64 positions from run `gi` on; true when one of them is feasible
+        // looks at 64 positions from run `gi` on (from further back at the end of the row: what lies
+        // before the first run that passes is infeasible anyway, its runs failed the bound); all
+        // addresses are a scalar start plus the lane
         const auto visit = [&](int gi) {
-            const int p = gi * kMemoP + lane, pc = min(p, rv.nblk * kWave - 1);
-            const float T = fmaf(c0j, kappa_of(rv.posK[pc], rv.Lf), rv.E[pc]);
-            const unsigned long long hit = __ballot(p == pc && T <= Dj);
+            const int start = min(gi * kMemoP, rv.nblk * kWave - kWave);
+            const float T = fmaf(c0j, kappa_of(rv.posK[start + lane], rv.Lf), rv.E[start + lane]);
+            const unsigned long long hit = __ballot(T <= Dj);
             if (hit) {
                 const int fl = __ffsll((long long)hit) - 1;
-                const float Tf = readlane_f(T, fl);
-                if (lane == j) { foundP = gi * kMemoP + fl; foundT = Tf; }
+                writelane_at(foundP, start + fl, j);
+                writelane_at(foundT, readlane_f(T, fl), j);
                 found = true;
             }
         };
