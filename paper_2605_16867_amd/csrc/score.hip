@@ -933,7 +933,8 @@ constexpr int kXcdRun = 8;     // workgroups in a row that stay on one XCD
 
 // One wave per tile: up to kTileReq requests of one length against all
 // instances.  Lane = position in capability order within a block of 64; the
-// requests' prefill lengths are wave-uniform scalars.
+// requests' prefill lengths are wave-uniform (scalar registers, and for half of
+// them a vector register as well, see kVecReq).
 //
 // Main pass, per pair: T = E + c0 * kappa (one multiply-add) folded into the
 // request's running minimum per lane (one three-way minimum per two pairs).
@@ -942,7 +943,9 @@ constexpr int kXcdRun = 8;     // workgroups in a row that stay on one XCD
 // feasible instance are looked at again, for their first one in capability
 // order (the just-enough choice).  The others take the instance of the minimum,
 // found by recomputing the positions of the lane that holds it (the earliest
-// position in capability order among equal minima).
+// position in capability order among equal minima).  The lanes' own request
+// records (budget, excluded instance, index in the caller's arrays) are read
+// only after the main pass and the minima.
 //
 // kW waves per workgroup, six waves per SIMD (80 vector registers: the 32
 // running minima, two sets of operands in flight and the epilogue's
