@@ -902,11 +902,22 @@ __device__ __forceinline__ void main_pass(const RowView& rv, const float (&c0)[k
     };
     auto fold = [&](const Step& st) {
         const float ka = kappa_of(st.Ka, rv.Lf), kb = kappa_of(st.Kb, rv.Lf);
+        // in pairs of requests, one with its length in a vector register and one in a scalar
+        // register: four multiply-adds, then the two minima (a minimum right behind the
+        // multiply-adds it reads waits for them)
+        static_assert(kVecReq * 2 == kTileReq, "request j (vector operand) goes with request j + kVecReq (scalar)");
 #pragma unroll
-        for (int j = 0; j < kN; ++j) {
-            const float c = j < kVecReq ? c0v[j] : c0[j];
-            const float Ta = fmaf(c, ka, st.Ea), Tb = fmaf(c, kb, st.Eb);
-            minT[j] = fminf(fminf(minT[j], Ta), Tb);
+        for (int j = 0; j < (kN < kVecReq ? kN : kVecReq); ++j) {
+            const int jv = j, js = j + kVecReq;
+            float Ta = fmaf(c0v[jv], ka, st.Ea), Tb = fmaf(c0v[jv], kb, st.Eb);
+            if (js < kN) {
+                float Ua = fmaf(c0[js], ka, st.Ea), Ub = fmaf(c0[js], kb, st.Eb);
+                asm volatile("" : "+v"(Ta), "+v"(Tb), "+v"(Ua), "+v"(Ub));
+                minT[jv] = fminf(fminf(minT[jv], Ta), Tb);
+                minT[js] = fminf(fminf(minT[js], Ua), Ub);
+            } else {
+                minT[jv] = fminf(fminf(minT[jv], Ta), Tb);
+            }
         }
     };
     // the prefetch is unconditional (past the end it re-reads the last step), so that the
