@@ -479,15 +479,19 @@ __device__ inline void writelane(int& dst, int uniform_value)
 
 // Put a wave-uniform value into the lane whose (wave-uniform) number is only
 // known at run time: the lane select travels in m0, the value in a scalar
-// register.
+// register.  m0 belongs to the compiler, so it is saved and put back.
 __device__ inline void writelane_at(float& dst, float uniform_value, int uniform_lane)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0" : "+v"(dst) : "s"(uniform_value), "s"(uniform_lane) : "m0");
+    int saved_m0;
+    asm volatile("s_mov_b32 %1, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tv_writelane_b32 %0, %2, m0\n\ts_mov_b32 m0, %1"
+                 : "+v"(dst), "=&s"(saved_m0) : "s"(uniform_value), "s"(uniform_lane));
 }
 
 __device__ inline void writelane_at(int& dst, int uniform_value, int uniform_lane)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0" : "+v"(dst) : "s"(uniform_value), "s"(uniform_lane) : "m0");
+    int saved_m0;
+    asm volatile("s_mov_b32 %1, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tv_writelane_b32 %0, %2, m0\n\ts_mov_b32 m0, %1"
+                 : "+v"(dst), "=&s"(saved_m0) : "s"(uniform_value), "s"(uniform_lane));
 }
 
 // Requests kJ0 .. kJ0+3 of a tile: their least latency over the wave and the
@@ -973,7 +977,7 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     extern __shared__ float2 lds_posK[];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int NT = a.totals[2], U = a.totals[1];
+    const int NT = a.totals[2];
     // consecutive tiles share a table row: keep them on one XCD (workgroups go round-robin over 8)
     // in runs of kXcdRun workgroups' worth of tiles, dealt to the XCDs in turn: tiles get cheaper
     // towards the long lengths (few requests each), and equal eighths of the tiles are not equal work
