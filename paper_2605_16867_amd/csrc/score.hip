@@ -916,7 +916,7 @@ __device__ __forceinline__ void main_pass(const RowView& rv, const float (&c0)[k
             float Ta = fmaf(c0v[jv], ka, st.Ea), Tb = fmaf(c0v[jv], kb, st.Eb);
             if (js < kN) {
                 float Ua = fmaf(c0[js], ka, st.Ea), Ub = fmaf(c0[js], kb, st.Eb);
-                asm volatile("" : "+v"(Ta), "+v"(Tb), "+v"(Ua), "+v"(Ub));
+                __builtin_amdgcn_sched_barrier(0);      // (the four multiply-adds stay ahead of the two minima)
                 minT[jv] = fminf(fminf(minT[jv], Ta), Tb);
                 minT[js] = fminf(fminf(minT[js], Ua), Ub);
             } else {
