@@ -533,7 +533,7 @@ __device__ inline void tile_minima4(const float (&minT)[kTileReq], float& Tm, in
 // inputs and the first DPP read.
 __device__ inline float tile_minima_all(const float (&m)[kTileReq], int lane)
 {
-    const bool b0 = lane & 1, b1 = lane & 2, b2 = lane & 4, b3 = lane & 8, b4 = lane & 16;
+    const bool b0 = lane & 1, b1 = lane & 2, b4 = lane & 16;
     float r1[16], r2[8], r3[4], r4[2];
     // eight minima: outputs %0-%7, what each lane sends %8-%15, what it keeps %16-%23
 #define GR_MIN8(o, sd, kp, ctrl)                                                                                     \
@@ -572,39 +572,27 @@ __device__ inline float tile_minima_all(const float (&m)[kTileReq], int lane)
         GR_MIN8(r2, send, keep, "quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf");
     }
 #undef GR_MIN8
-    {   // lane ^ 4: lanes 0-3 and 8-11 of a row of 16 read four lanes up, the others four lanes down
-        float keep[4], send[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            keep[k] = b2 ? r2[2 * k + 1] : r2[2 * k];
-            send[k] = b2 ? r2[2 * k] : r2[2 * k + 1];
-        }
-        asm volatile("s_nop 1\n\t"
-                     "v_min_f32_dpp %0, %4, %8 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
-                     "v_min_f32_dpp %1, %5, %9 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
-                     "v_min_f32_dpp %2, %6, %10 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
-                     "v_min_f32_dpp %3, %7, %11 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
-                     "v_min_f32_dpp %0, %4, %8 row_shr:4 row_mask:0xf bank_mask:0xa\n\t"
-                     "v_min_f32_dpp %1, %5, %9 row_shr:4 row_mask:0xf bank_mask:0xa\n\t"
-                     "v_min_f32_dpp %2, %6, %10 row_shr:4 row_mask:0xf bank_mask:0xa\n\t"
-                     "v_min_f32_dpp %3, %7, %11 row_shr:4 row_mask:0xf bank_mask:0xa"
-                     : "=&v"(r3[0]), "=&v"(r3[1]), "=&v"(r3[2]), "=&v"(r3[3])
-                     : "v"(send[0]), "v"(send[1]), "v"(send[2]), "v"(send[3]),
-                       "v"(keep[0]), "v"(keep[1]), "v"(keep[2]), "v"(keep[3]));
-    }
-    {   // lane ^ 8: a rotation of the row of 16 by 8
-        float keep[2], send[2];
-#pragma unroll
-        for (int k = 0; k < 2; ++k) {
-            keep[k] = b3 ? r3[2 * k + 1] : r3[2 * k];
-            send[k] = b3 ? r3[2 * k] : r3[2 * k + 1];
-        }
-        asm volatile("s_nop 1\n\t"
-                     "v_min_f32_dpp %0, %2, %4 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
-                     "v_min_f32_dpp %1, %3, %5 row_ror:8 row_mask:0xf bank_mask:0xf"
-                     : "=&v"(r4[0]), "=&v"(r4[1])
-                     : "v"(send[0]), "v"(send[1]), "v"(keep[0]), "v"(keep[1]));
-    }
+    // lane ^ 4 and lane ^ 8: the lanes that keep the even request of a pair are whole banks of four
+    // lanes (0-3 and 8-11 of a row of 16, then 0-7), so each output takes two minima that write
+    // only their banks and read the register they keep both here and in the partner: no selects.
+    asm volatile("s_nop 1\n\t"
+                 "v_min_f32_dpp %0, %4, %4 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
+                 "v_min_f32_dpp %1, %6, %6 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
+                 "v_min_f32_dpp %2, %8, %8 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
+                 "v_min_f32_dpp %3, %10, %10 row_shl:4 row_mask:0xf bank_mask:0x5\n\t"
+                 "v_min_f32_dpp %0, %5, %5 row_shr:4 row_mask:0xf bank_mask:0xa\n\t"
+                 "v_min_f32_dpp %1, %7, %7 row_shr:4 row_mask:0xf bank_mask:0xa\n\t"
+                 "v_min_f32_dpp %2, %9, %9 row_shr:4 row_mask:0xf bank_mask:0xa\n\t"
+                 "v_min_f32_dpp %3, %11, %11 row_shr:4 row_mask:0xf bank_mask:0xa"
+                 : "=&v"(r3[0]), "=&v"(r3[1]), "=&v"(r3[2]), "=&v"(r3[3])
+                 : "v"(r2[0]), "v"(r2[1]), "v"(r2[2]), "v"(r2[3]), "v"(r2[4]), "v"(r2[5]), "v"(r2[6]), "v"(r2[7]));
+    asm volatile("s_nop 1\n\t"
+                 "v_min_f32_dpp %0, %2, %2 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+                 "v_min_f32_dpp %1, %4, %4 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+                 "v_min_f32_dpp %0, %3, %3 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+                 "v_min_f32_dpp %1, %5, %5 row_ror:8 row_mask:0xf bank_mask:0xc"
+                 : "=&v"(r4[0]), "=&v"(r4[1])
+                 : "v"(r3[0]), "v"(r3[1]), "v"(r3[2]), "v"(r3[3]));
     const float keep = b4 ? r4[1] : r4[0], send = b4 ? r4[0] : r4[1];
     // lane ^ 16 by a swizzle in bit mode (and 0x1f, or 0, xor 0x10), lane ^ 32 by a permute; both
     // values come back as they were stored, so the minima below need no canonicalising
