@@ -45,7 +45,7 @@ SCAN_EXTRA_BYTES_PER_ENTRY = 5.0
 # HBM bytes per launch of the dominant kernel (k_tile, migration launch of the "heavy" fleet) from
 # the rocprofv3 counter passes summarised under profiles/, scaled by the plain-copy calibration;
 # None whenever that kernel has changed since the counters were taken.
-TILE_MIGRATE_HEAVY_TRAFFIC_BYTES = int((249.0 + 132.4) * 2**20)   # fetch + write MiB per launch
+TILE_MIGRATE_HEAVY_TRAFFIC_BYTES = int((249.2 + 132.4) * 2**20)   # fetch + write MiB per launch
 
 
 def parse():
