@@ -295,10 +295,7 @@ int gr_set_batch_cap(gr_fleet* f, const int32_t* cap);
  *               pair by pair when n_req * (n_inst rounded up to 128) is at
  *               most this and n_req <= 4096.  0: never.  Default 262 144.
  * gr_score_route_cached and gr_risk_scan always take the grouped path.
- * Equal latencies: pair by pair the lowest instance index wins; the grouped
- * path prefers the earlier position in capability order among positions 64
- * apart (the two differ only for instances of different speed with
- * bit-identical latency).
+ * Equal latencies go to the lowest instance index either way.
  */
 int gr_set_small_batch_pairs(gr_fleet* f, int64_t max_pairs);
 

@@ -45,6 +45,7 @@ def _load():
         lib.gro_step_table.argtypes = [p, C.c_int32, p]
         lib.gro_pair_T.argtypes = [p, C.c_int64] + [p] * 6
         lib.gro_route.argtypes = [p, C.c_int64] + [p] * 11
+        lib.gro_band.argtypes = [p, C.c_int64] + [p] * 8 + [C.c_double] + [p] * 7
         lib.gro_threads.restype = C.c_int32
         _lib = lib
     return _lib
@@ -72,6 +73,18 @@ class Routing:
     slack: np.ndarray       # float64, D - T(r, chosen)
     fallback: np.ndarray    # uint8, 1 when no instance was feasible
     T: np.ndarray           # float64, T(r, chosen)
+
+
+@dataclass
+class Band:
+    """Per request, what decides whether Alg. 1's answer survives a relative error eps
+    on every latency (see gro_band in the C file); ranks are positions in capability order."""
+    sure: np.ndarray        # int32, first surely feasible rank, n_inst if none
+    maybe: np.ndarray       # int32, first possibly feasible rank, n_inst if none
+    tmin: np.ndarray        # float64, least latency over the allowed instances
+    near: np.ndarray        # int32, instances within 2 eps of the least latency
+    equal: np.ndarray       # int32, instances whose latency equals the least one bit for bit
+    picked_T: np.ndarray    # float64, latency of the pair (request, picked instance)
 
 
 class SimulatedFleet:
@@ -142,6 +155,20 @@ class SimulatedFleet:
                           _ptr(ho), _ptr(hi), _ptr(hl),
                           _ptr(r.inst), _ptr(r.slack), _ptr(r.fallback), _ptr(r.T))
         return r
+
+    def band(self, c0, length, deadline, picked, eps: float, exclude=None, hits=None) -> Band:
+        c0, length, deadline, picked = _i32(c0), _i32(length), _f64(deadline), _i32(picked)
+        n = len(c0)
+        ex = None if exclude is None else _i32(exclude)
+        ho, hi, hl = self._hits(hits)
+        rank = _i32(self.rank)
+        b = Band(np.zeros(n, np.int32), np.zeros(n, np.int32), np.zeros(n, np.float64),
+                 np.zeros(n, np.int32), np.zeros(n, np.int32), np.zeros(n, np.float64))
+        _load().gro_band(self._h, n, _ptr(c0), _ptr(length), _ptr(deadline), _ptr(ex),
+                         _ptr(ho), _ptr(hi), _ptr(hl), _ptr(rank), float(eps), _ptr(picked),
+                         _ptr(b.sure), _ptr(b.maybe), _ptr(b.tmin), _ptr(b.near), _ptr(b.equal),
+                         _ptr(b.picked_T))
+        return b
 
 
 def simulate(fleet, act_rem=None) -> SimulatedFleet:

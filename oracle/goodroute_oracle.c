@@ -316,6 +316,60 @@ void gro_route(const gro_fleet *f, int64_t n_req, const int32_t *c0, const int32
     }
 }
 
+/*
+ * How firmly Alg. 1's answer for each request stands when every latency may be
+ * off by a relative eps (the GPU forms T in fp32): the same exhaustive scan as
+ * gro_route, keeping per request what a comparison of another implementation's
+ * answer needs.  rank[g] is the position of instance g in capability order
+ * (largest d_g first, equal d_g by index); "first" below means smallest rank.
+ *
+ *   sure[r]    rank of the first instance with T*(1+eps) <= D (feasible whatever the error), n_inst if none
+ *   maybe[r]   rank of the first instance with T*(1-eps) <= D (feasible for some error), n_inst if none
+ *   tmin[r]    smallest T over the allowed instances (+inf if none is allowed)
+ *   near[r]    number of allowed instances with T <= tmin*(1+2 eps)
+ *   equal[r]   number of allowed instances with T == tmin, bit for bit
+ *   picked_T[r]  T(r, picked[r]) (+inf when picked[r] is no allowed instance)
+ *
+ * It decides nothing itself.
+ */
+void gro_band(const gro_fleet *f, int64_t n_req, const int32_t *c0, const int32_t *len,
+              const double *deadline, const int32_t *exclude,
+              const int32_t *hit_off, const int32_t *hit_inst, const int32_t *hit_len,
+              const int32_t *rank, double eps, const int32_t *picked,
+              int32_t *sure, int32_t *maybe, double *tmin, int32_t *near, int32_t *equal,
+              double *picked_T)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < n_req; ++r) {
+        int32_t ex = exclude ? exclude[r] : -1;
+        double D = deadline[r];
+        int32_t s1 = f->n_inst, p1 = f->n_inst;
+        double lo = INFINITY;
+        for (int32_t g = 0; g < f->n_inst; ++g) {
+            if (g == ex) continue;
+            double T = pair_T(f, g, c0[r], len[r],
+                              reusable_prefix(hit_off, hit_inst, hit_len, r, g, c0[r]));
+            if (T * (1.0 + eps) <= D && rank[g] < s1) s1 = rank[g];
+            if (T * (1.0 - eps) <= D && rank[g] < p1) p1 = rank[g];
+            if (T < lo) lo = T;
+        }
+        int32_t n_near = 0, n_equal = 0;
+        for (int32_t g = 0; g < f->n_inst; ++g) {
+            if (g == ex) continue;
+            double T = pair_T(f, g, c0[r], len[r],
+                              reusable_prefix(hit_off, hit_inst, hit_len, r, g, c0[r]));
+            if (T <= lo * (1.0 + 2.0 * eps)) ++n_near;
+            if (T == lo) ++n_equal;
+        }
+        int32_t pk = picked[r];
+        sure[r] = s1; maybe[r] = p1; tmin[r] = lo; near[r] = n_near; equal[r] = n_equal;
+        picked_T[r] = (pk >= 0 && pk < f->n_inst && pk != ex)
+                          ? pair_T(f, pk, c0[r], len[r],
+                                   reusable_prefix(hit_off, hit_inst, hit_len, r, pk, c0[r]))
+                          : INFINITY;
+    }
+}
+
 int32_t gro_threads(void)
 {
     int32_t n = 1;

@@ -945,8 +945,9 @@ constexpr int kXcdRun = 8;     // workgroups in a row that stay on one XCD
 // feasibility test of every pair is implied; only requests that have a
 // feasible instance are looked at again, for their first one in capability
 // order (the just-enough choice).  The others take the instance of the minimum,
-// found by recomputing the positions of the lane that holds it (the earliest
-// position in capability order among equal minima).  The lanes' own request
+// found by recomputing the positions of the lane that holds it; equal minima
+// (in several lanes or at several positions of one lane) are redone one by one,
+// so that ties go to the lowest instance index.  The lanes' own request
 // records (budget, excluded instance, index in the caller's arrays) are read
 // only after the main pass and the minima.
 //
@@ -1083,7 +1084,10 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     // if they are equal, and T >= min) and huge elsewhere; the least key is the earliest such block.
     // That is three instructions of the class that issues two per slot and half a three-way
     // minimum per block, instead of a compare and a select.
-    int firstB = 0x7fffffff;
+    // A second key of the same kind with the blocks counted down gives the latest such block: the
+    // two differ when the lane holds the minimum at more than one position (different instances
+    // with the same latency), and then the tie goes to the lowest instance index, one by one.
+    int firstB = 0x7fffffff, lastB = -1;
     if (__ballot(mine && foundP < 0)) {
         const int lw = s_win & (kWave - 1), half = lane >> 5;
         const float* __restrict__ pe = rv.E + half * kWave + lw;
@@ -1092,19 +1096,25 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
 #pragma unroll 8
         for (int i = 0; i < rv.nblk / 2; ++i) {       // block 2 i + half
             const float Tc = fmaf(s_c0, kappa_of(pk[i * 2 * kWave], rv.Lf), pe[i * 2 * kWave]);
-            key = fminf(key, fmaf(Tc - s_Tm, 0x1p100f, blk));
+            const float off = Tc - s_Tm;
+            key = fminf(key, fmaf(off, 0x1p100f, blk));
+            keyL = fminf(keyL, fmaf(off, 0x1p100f, back));
             blk += 2.0f;
         }
-        if (key < 0x1p30f) firstB = (int)key;
+        if (key < 0x1p30f) { firstB = (int)key; lastB = rv.nblk - (int)keyL; }
+        float back = (float)(rv.nblk - half), keyL = 0x1p100f;
     }
     firstB = min(firstB, __shfl_xor(firstB, 32, kWave));
     const int candP = firstB < rv.nblk ? firstB * kWave + (win & (kWave - 1)) : -1;
-    // equal minima in several lanes and a minimum on the excluded instance: one by one
+    // equal minima (in several lanes, or at several positions of one) and a minimum on the
+    // excluded instance: one by one
     const bool slow = mine && (foundP >= 0 ? foundP == rec.pex
-                                           : (win == kWave || candP < 0 || candP == rec.pex));
+            back -= 2.0f;
+                                           : (win == kWave || candP < 0 || candP == rec.pex || lastB != firstB));
 
     int p = foundP >= 0 ? foundP : candP;
     float T = foundP >= 0 ? foundT : Tm;
+    lastB = max(lastB, __shfl_xor(lastB, 32, kWave));
     bool found = foundP >= 0;
 
     unsigned long long redo = __ballot(slow);

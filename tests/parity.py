@@ -47,9 +47,12 @@ def classify_choices(T, D, rank, exclude, picked):
     none_allowed = ~np.isfinite(Tmin)
     want[none_allowed] = -1
 
-    srt = np.sort(T, axis=1)
-    second = srt[:, 1] if M > 1 else np.full(n, np.inf)
-    robust_fb = second > Tmin * (1 + 2 * EPS)
+    # nothing feasible: decided when every latency within 2 eps of the smallest one equals it bit
+    # for bit (one instance, or exact ties, which go to the lowest index)
+    with np.errstate(invalid="ignore"):
+        near = (T <= (Tmin * (1 + 2 * EPS))[:, None]).sum(axis=1)
+        equal = (T == Tmin[:, None]).sum(axis=1)
+    robust_fb = near == equal
     robust = np.where(p1 < M, p1 == s1, robust_fb) | none_allowed
 
     pos = np.empty(M, dtype=np.int64)
@@ -88,6 +91,54 @@ def check_choices(name, T, D, rank, exclude, picked, slack, rep, fallback=None):
     rep[name + "_differ"] = int((picked != want).sum())
     rep[name + "_n"] = int(len(picked))
     rep[name + "_feasible_frac"] = float(np.mean((T <= D[:, None]).any(axis=1))) if len(D) else 0.0
+    return want
+
+
+def judge_with_band(band, D, rank, picked):
+    """The same verdicts as classify_choices from the per-request summary of
+    ``oracle.SimulatedFleet.band`` (no [n, M] matrix): (robust, admissible, fallback bit or -1)."""
+    M = len(rank)
+    s1, p1, Tmin, pT = band.sure.astype(np.int64), band.maybe.astype(np.int64), band.tmin, band.picked_T
+    none_allowed = ~np.isfinite(Tmin)
+    robust = np.where(p1 < M, p1 == s1, band.near == band.equal) | none_allowed
+    ppos = np.where(picked >= 0, np.asarray(rank, dtype=np.int64)[np.maximum(picked, 0)], M)
+    with np.errstate(invalid="ignore"):
+        in_PF = np.isfinite(pT) & (pT * (1 - EPS) <= D)
+        near_min = np.isfinite(pT) & (pT <= Tmin * (1 + 2 * EPS))
+    adm = np.where(s1 < M, in_PF & (ppos <= s1), np.where(p1 < M, in_PF | near_min, near_min))
+    adm = np.where(none_allowed, picked == -1, adm)
+    fb_known = np.where(s1 < M, 0, np.where(p1 == M, 1, -1))
+    return robust, adm, fb_known
+
+
+def check_choices_all(name, sim, c0, ln, D, exclude, hits, picked, slack, rep, fallback=None):
+    """Every request of a batch of any size against the reference's exhaustive scan:
+    the reference's own choice (Alg. 1) and, per request, how firmly it stands."""
+    ref = sim.route(c0, ln, D, exclude=exclude, hits=hits)
+    band = sim.band(c0, ln, D, picked, EPS, exclude=exclude, hits=hits)
+    want = ref.inst.astype(np.int64)
+    robust, adm, fb_known = judge_with_band(band, D, sim.rank, picked)
+    if fallback is not None:
+        known = fb_known >= 0
+        assert np.array_equal(fallback[known], fb_known[known]), f"{name}: fallback bit wrong outside the band"
+        assert np.array_equal(ref.fallback[known], fb_known[known]), f"{name}: reference scan and band disagree"
+    bad = robust & (picked != want)
+    assert not bad.any(), f"{name}: {bad.sum()} robust choices differ, first at {np.flatnonzero(bad)[:5]}"
+    assert adm[~robust].all(), f"{name}: {(~adm[~robust]).sum()} ambiguous choices not admissible"
+    ok = picked >= 0
+    Tp = band.picked_T[ok]
+    got_s, want_s = slack[ok].astype(np.float64), D[ok] - Tp
+    with np.errstate(invalid="ignore"):
+        err = np.abs(got_s - want_s)
+        tol = EPS * np.maximum(Tp, np.abs(D[ok])) + 1e-30
+        fine = (err <= tol) | (got_s == want_s) | (np.isnan(got_s) & np.isnan(want_s))
+    assert np.all(fine), f"{name}: {np.sum(~fine)} slacks beyond tolerance"
+    assert np.all(slack[~ok] == 0.0)
+    rep[name + "_ambiguous"] = int((~robust).sum())
+    rep[name + "_differ"] = int((picked != want).sum())
+    rep[name + "_n"] = int(len(picked))
+    rep[name + "_exact_ties"] = int((band.equal > 1).sum())
+    rep[name + "_feasible_frac"] = float(1.0 - ref.fallback.mean()) if len(D) else 0.0
     return want
 
 
@@ -184,6 +235,7 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
     assert np.array_equal(rk.cpu().numpy(), sim.rank), "capability rank differs"
 
     # ---- step 2: route
+    whole = hasattr(sim, "band")       # the C reference scans a batch of any size; the numpy blend is sampled
     if R:
         ex_np = None if exclude is None else np.ascontiguousarray(exclude, dtype=np.int32)
         inst = torch.full((R,), -7, dtype=torch.int32, device=dev)
@@ -192,31 +244,62 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
         want_T = R * M <= full_T_limit
         outT = torch.zeros(R * M, dtype=torch.float32, device=dev) if want_T else None
         ex_t = None if ex_np is None else torch.from_numpy(ex_np).to(dev)
-        if hits is None:
-            h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, slack,
-                             exclude_inst=ex_t, out_fallback=fb, out_T=outT)
-        else:
-            ht = [torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev) for x in hits]
-            h.gr_score_route_cached(d["in_prompt"], d["in_len"], d["in_budget"], ht[0], ht[1], ht[2],
-                                    inst, slack, exclude_inst=ex_t, out_fallback=fb, out_T=outT)
-        torch.cuda.synchronize()
+        ht = None if hits is None else [torch.from_numpy(np.ascontiguousarray(x, dtype=np.int32)).to(dev) for x in hits]
+
+        def route(c0_t, len_t, bud_t, ex_sub, h_sub, o_inst, o_slack, o_fb, o_T):
+            if h_sub is None:
+                h.gr_score_route(c0_t, len_t, bud_t, o_inst, o_slack, exclude_inst=ex_sub, out_fallback=o_fb, out_T=o_T)
+            else:
+                h.gr_score_route_cached(c0_t, len_t, bud_t, h_sub[0], h_sub[1], h_sub[2], o_inst, o_slack,
+                                        exclude_inst=ex_sub, out_fallback=o_fb, out_T=o_T)
+            torch.cuda.synchronize()
+
+        route(d["in_prompt"], d["in_len"], d["in_budget"], ex_t, ht, inst, slack, fb, outT)
+        g_inst, g_slack, g_fb = inst.cpu().numpy().astype(np.int64), slack.cpu().numpy(), fb.cpu().numpy()
         idx = np.arange(R) if sample is None or sample >= R else np.sort(rng.choice(R, sample, replace=False))
-        sub_hits = None if hits is None else sub_csr(hits, idx)
-        T = sim.pair_T(fl.in_prompt[idx], fl.in_len[idx], hits=sub_hits)
-        D = fl.in_budget[idx].astype(np.float64)
-        if want_T:
-            e = rel_err(outT.cpu().numpy().reshape(R, M)[idx], T)
-            assert e.max() <= EPS, f"pair latency rel err {e.max():.3g}"
-            rep["pair_T_rel_err"] = float(e.max())
-        picked = inst.cpu().numpy()[idx].astype(np.int64)
-        want = check_choices("route", T, D, sim.rank, None if ex_np is None else ex_np[idx], picked,
-                             slack.cpu().numpy()[idx], rep, fallback=fb.cpu().numpy()[idx])
-        ref = sim.route(fl.in_prompt[idx], fl.in_len[idx], D,
-                        exclude=None if ex_np is None else ex_np[idx], hits=sub_hits)
-        if hits is not None:
-            rep["route_moved_by_hits"] = int((ref.inst != sim.route(
-                fl.in_prompt[idx], fl.in_len[idx], D, exclude=None if ex_np is None else ex_np[idx]).inst).sum())
-        assert np.array_equal(ref.inst, want), "reference scan and classifier disagree"
+        D_all = fl.in_budget.astype(np.float64)
+        if whole:
+            check_choices_all("route", sim, fl.in_prompt, fl.in_len, D_all, ex_np, hits, g_inst, g_slack, rep,
+                              fallback=g_fb)
+            if hits is not None:
+                rep["route_moved_by_hits"] = int((sim.route(fl.in_prompt, fl.in_len, D_all, exclude=ex_np, hits=hits).inst
+                                                  != sim.route(fl.in_prompt, fl.in_len, D_all, exclude=ex_np).inst).sum())
+        # every pair's latency: of the whole batch where that fits, else of a slice scored again on its own
+        t_idx = (np.arange(R) if whole else idx) if want_T else np.sort(rng.choice(R, max(1, min(R, full_T_limit // M)), replace=False))
+        sub_hits = None if hits is None else sub_csr(hits, t_idx)
+        if not want_T:
+            ti = torch.from_numpy(t_idx).to(dev)
+            n_t = len(t_idx)
+            s_inst = torch.full((n_t,), -7, dtype=torch.int32, device=dev)
+            s_slack = torch.zeros(n_t, dtype=torch.float32, device=dev)
+            s_fb = torch.zeros(n_t, dtype=torch.uint8, device=dev)
+            s_T = torch.zeros(n_t * M, dtype=torch.float32, device=dev)
+            route(d["in_prompt"][ti].contiguous(), d["in_len"][ti].contiguous(), d["in_budget"][ti].contiguous(),
+                  None if ex_t is None else ex_t[ti].contiguous(),
+                  None if sub_hits is None else [torch.from_numpy(x).to(dev) for x in sub_hits],
+                  s_inst, s_slack, s_fb, s_T)
+            # the same requests in a batch of their own are decided the same way
+            assert np.array_equal(s_inst.cpu().numpy(), g_inst[t_idx]), "a slice of the batch is routed differently"
+            assert np.array_equal(s_fb.cpu().numpy(), g_fb[t_idx])
+            got_T = s_T.cpu().numpy().reshape(n_t, M)
+        else:
+            got_T = outT.cpu().numpy().reshape(R, M)[t_idx]
+        T = sim.pair_T(fl.in_prompt[t_idx], fl.in_len[t_idx], hits=sub_hits)
+        e = rel_err(got_T, T)
+        assert e.max() <= EPS, f"pair latency rel err {e.max():.3g}"
+        rep["pair_T_rel_err"], rep["pair_T_checked"] = float(e.max()), int(T.size)
+        if not whole or len(t_idx) * M <= (1 << 24):
+            # the [n, M] classifier on the same rows (the only one there is for the blended reference)
+            rr = rep if not whole else {}
+            want = check_choices("route", T, D_all[t_idx], sim.rank, None if ex_np is None else ex_np[t_idx],
+                                 g_inst[t_idx], g_slack[t_idx], rr, fallback=g_fb[t_idx])
+            ref = sim.route(fl.in_prompt[t_idx], fl.in_len[t_idx], D_all[t_idx],
+                            exclude=None if ex_np is None else ex_np[t_idx], hits=sub_hits)
+            if hits is not None and not whole:
+                rep["route_moved_by_hits"] = int((ref.inst != sim.route(
+                    fl.in_prompt[t_idx], fl.in_len[t_idx], D_all[t_idx],
+                    exclude=None if ex_np is None else ex_np[t_idx]).inst).sum())
+            assert np.array_equal(ref.inst, want), "reference scan and classifier disagree"
 
     # ---- step 3: risk scan
     if na:
@@ -241,18 +324,26 @@ def run_and_check(fl, sample: Optional[int] = None, seed: int = 0, full_T_limit:
         bad = (gflag != rs.flag) & ~band
         assert not bad.any(), f"{bad.sum()} robust risk flags differ"
         rep["flag_ambiguous"] = int(band.sum())
+        rep["flag_n"] = int(na)
         rep["flag_frac"] = float(gflag.mean())
         assert int(nfl.item()) == int(gflag.sum()), "flag count differs from flags"
         gt, gs = tgt.cpu().numpy(), tsl.cpu().numpy()
         assert np.all(gt[gflag == 0] == -1) and np.all(gs[gflag == 0] == 0.0)
-        both = idx[(gflag[idx] == 1) & (rs.flag[idx] == 1)]
+        every = np.flatnonzero((gflag == 1) & (rs.flag == 1))
+        both = every if whole else idx[(gflag[idx] == 1) & (rs.flag[idx] == 1)]
         if len(both):
             inst_of = (np.searchsorted(fl.act_off, both, side="right") - 1).astype(np.int32)
             c0 = fl.act_prompt[both].astype(np.int64) + fl.act_gen[both]
-            T = rs.sim.pair_T(c0, fl.act_rem_refreshed[both])
-            want = check_choices("migrate", T, budget[both], rs.sim.rank, inst_of,
-                                 gt[both].astype(np.int64), gs[both], rep)
-            assert np.array_equal(want, rs.target[both]), "reference scan and classifier disagree"
+            if whole:
+                want = check_choices_all("migrate", rs.sim, c0, fl.act_rem_refreshed[both], budget[both], inst_of,
+                                         None, gt[both].astype(np.int64), gs[both], rep)
+                sub = np.isin(both, idx)         # the composed reference scan names the same targets
+                assert np.array_equal(want[sub], rs.target[both[sub]]), "reference scan and classifier disagree"
+            else:
+                T = rs.sim.pair_T(c0, fl.act_rem_refreshed[both])
+                want = check_choices("migrate", T, budget[both], rs.sim.rank, inst_of,
+                                     gt[both].astype(np.int64), gs[both], rep)
+                assert np.array_equal(want, rs.target[both]), "reference scan and classifier disagree"
             assert np.all(gt[both] != inst_of) or M == 1
     assert h.gr_device_status() == 0, "device status bits raised on in-contract input"
     h.close()

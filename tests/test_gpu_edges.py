@@ -9,6 +9,7 @@ import pytest
 import oracle
 from paper_2605_16867_amd import binding, workloads
 from tests import parity
+from tests.fleets import CLASSES, fleet, rand_entries, solo, two_equal_minima_in_one_lane
 
 pytestmark = pytest.mark.gpu
 
@@ -20,43 +21,6 @@ def scoring_layout(request):
     parity.SMALL_BATCH_PAIRS = None if request.param == "auto" else 0
     yield
     parity.SMALL_BATCH_PAIRS = None
-
-
-CLASSES = [(2e-5, 0.012, 2e-4, 2e-8), (5e-5, 0.025, 4e-4, 5e-8), (1.2e-4, 0.05, 8e-4, 1e-7)]
-
-
-def fleet(inst_class, actives, queued, incoming, budgets, act_budget=None, refreshed=None,
-          classes=CLASSES, max_len=4096):
-    """actives: per instance arrays (prompt, gen, rem) as [n,3]; queued: [n,2]; incoming: [R,2]."""
-    i32 = lambda a: np.ascontiguousarray(a, dtype=np.int32)
-    A = [np.asarray(a, dtype=np.int64).reshape(-1, 3) for a in actives]
-    Q = [np.asarray(q, dtype=np.int64).reshape(-1, 2) for q in queued]
-    a = np.concatenate(A) if A else np.zeros((0, 3), np.int64)
-    q = np.concatenate(Q) if Q else np.zeros((0, 2), np.int64)
-    inc = np.asarray(incoming, dtype=np.int64).reshape(-1, 2)
-    names = ("delta", "alpha", "beta", "gamma")
-    na = len(a)
-    return SimpleNamespace(
-        coef={k: np.array([c[i] for c in classes], dtype=np.float64) for i, k in enumerate(names)},
-        inst_class=i32(inst_class), max_len=max_len,
-        act_off=i32(np.cumsum([0] + [len(x) for x in A])),
-        act_prompt=i32(a[:, 0]), act_gen=i32(a[:, 1]), act_rem=i32(a[:, 2]),
-        act_rem_refreshed=i32(a[:, 2] if refreshed is None else refreshed),
-        act_budget=np.ascontiguousarray(np.full(na, 1e9) if act_budget is None else act_budget,
-                                        dtype=np.float32),
-        q_off=i32(np.cumsum([0] + [len(x) for x in Q])),
-        q_prompt=i32(q[:, 0]), q_len=i32(q[:, 1]),
-        in_prompt=i32(inc[:, 0]), in_len=i32(inc[:, 1]),
-        in_budget=np.ascontiguousarray(budgets, dtype=np.float32))
-
-
-def rand_entries(rng, n, max_len=4096):
-    return np.stack([rng.integers(128, 2049, n), rng.integers(0, 201, n),
-                     np.clip(np.rint(rng.lognormal(5, 1, n)), 1, max_len)], axis=1)
-
-
-def solo(P, L, c=CLASSES[0]):
-    return c[0] * P + L * (c[1] + c[2]) + c[3] * (P * L + L * (L - 1) / 2)
 
 
 def test_empty_and_queue_only_instances():
@@ -101,6 +65,21 @@ def test_identical_instances_tie_to_lowest_index():
     torch.cuda.synchronize()
     assert (inst.cpu().numpy() == 1).all()       # instance 0 excluded: next lowest index
     h.close()
+
+
+def test_equal_minima_at_two_positions_of_one_lane_go_to_the_lowest_index():
+    """Two different instances, 64 positions apart in capability order (the same lane of the
+    scoring wave), with the same latency bit for bit and smaller than everybody else's: the
+    fallback choice is the lower index, whichever comes first in capability order."""
+    for between in (63, 127, 191):
+        fl = two_equal_minima_in_one_lane(between)
+        rep = parity.run_and_check(fl)
+        assert rep["route_exact_ties"] == 48 and rep["route_ambiguous"] == 0 and rep["route_differ"] == 0
+        # the same with either of the two barred: the other one
+        M = len(fl.inst_class)
+        for ex in (0, M - 1):
+            rep = parity.run_and_check(fl, exclude=np.full(len(fl.in_prompt), ex, dtype=np.int32))
+            assert rep["route_ambiguous"] == 0 and rep["route_differ"] == 0
 
 
 def test_single_instance_and_everything_excluded():

@@ -18,7 +18,6 @@ def scoring_layout(request):
     parity.SMALL_BATCH_PAIRS = None
 
 
-
 def report(name, rep):
     print(f"\n[{name}] " + " ".join(f"{k}={v}" for k, v in rep.items()), flush=True)
 
@@ -48,47 +47,6 @@ def test_route_with_exclusions():
     report("exclude", parity.run_and_check(fl, exclude=ex))
 
 
-def test_large_fleet_sampled():
-    fl = workloads.make_fleet(workloads.spec("large"))
-    report("large", parity.run_and_check(fl, sample=4096, full_T_limit=1 << 25))
-
-
-def test_large_fleet_loose_slo_sampled():
-    fl = workloads.make_fleet(workloads.spec("large", slo_scale=4.0, occupancy_jitter=True, seed=2))
-    report("large x4", parity.run_and_check(fl, sample=4096))
-
-
-def test_migrate_fleet_full_size_sampled():
-    """1 024 instances x 1 000 held requests, drifted lengths: flags of all 1 024 000
-    requests, targets of a sample."""
-    fl = workloads.make_fleet(workloads.spec("migrate"))
-    rep = parity.run_and_check(fl, sample=3000)
-    report("migrate", rep)
-    assert rep["flag_frac"] > 0.9
-
-
-def test_migrate_fleet_loose_slo():
-    fl = workloads.make_fleet(workloads.spec("migrate", slo_scale=8.0, n_incoming=20000, seed=4))
-    rep = parity.run_and_check(fl, sample=3000)
-    report("migrate x8", rep)
-    assert 0.05 < rep["flag_frac"] < 0.95 and rep["migrate_feasible_frac"] > 0.05
-
-
-def test_heavy_fleet_full_size_sampled():
-    """The benchmark's own configuration and launch shapes: 4 096 instances, 262 144
-    incoming, 2.1 M held requests; decisions of a sample against the reference."""
-    fl = workloads.make_fleet(workloads.spec("heavy"))
-    rep = parity.run_and_check(fl, sample=2048)
-    report("heavy", rep)
-
-
-def test_heavy_fleet_loose_slo():
-    fl = workloads.make_fleet(workloads.spec("heavy", slo_scale=16.0, n_incoming=65536, seed=9))
-    rep = parity.run_and_check(fl, sample=2048)
-    report("heavy x16", rep)
-    assert rep["route_feasible_frac"] > 0.3
-
-
 # --------------------------------------------------------------------------- cached prefixes (Eq. 2's H)
 @pytest.mark.parametrize("scale", [1.0, 2.0, 8.0])
 def test_mid_fleet_with_cached_prefixes(scale):
@@ -110,19 +68,6 @@ def test_cached_prefixes_with_exclusions():
     report("prefixes + exclude", parity.run_and_check(fl, exclude=ex, hits=hits))
 
 
-def test_large_fleet_with_cached_prefixes_sampled():
-    fl = workloads.make_fleet(workloads.spec("large", slo_scale=3.0, seed=23))
-    hits = workloads.cached_prefixes(fl, mean_hits=2.0, seed=3)
-    report("large x3 + prefixes", parity.run_and_check(fl, sample=4096, hits=hits))
-
-
-def test_heavy_fleet_with_cached_prefixes_sampled():
-    fl = workloads.make_fleet(workloads.spec("heavy"))
-    hits = workloads.cached_prefixes(fl, mean_hits=2.0, seed=4)
-    rep = parity.run_and_check(fl, sample=2048, hits=hits)
-    report("heavy + prefixes", rep)
-
-
 # --------------------------------------------------------------------------- EMA-smoothed black-box status (Sec. 3.3)
 @pytest.mark.parametrize("lam", [0.25, 1.0])
 def test_mid_fleet_blended_with_black_box_status(lam):
@@ -142,18 +87,14 @@ def test_blend_with_prefixes_and_exclusions():
     report("mid blend 0.6 + prefixes + exclude", rep)
 
 
-def test_heavy_fleet_blended_sampled():
-    fl = workloads.make_fleet(workloads.spec("heavy"))
-    rep = parity.run_and_check(fl, sample=1024, blackbox=(workloads.observed_status(fl, 2, seed=3), 0.5))
-    report("heavy blend 0.5", rep)
-
-
 def test_blend_zero_is_the_white_box_model_and_errors():
     from paper_2605_16867_amd import binding
     fl = workloads.make_fleet(workloads.spec("tiny"))
     rep0 = parity.run_and_check(fl)
     rep1 = parity.run_and_check(fl, blackbox=(workloads.observed_status(fl, 1, seed=4), 0.0))
-    assert rep0 == rep1
+    for k in ("finish_rel_err", "pair_T_rel_err", "route_differ", "route_ambiguous", "flag_frac", "flag_ambiguous",
+              "migrate_differ", "migrate_ambiguous", "migrate_n"):
+        assert rep0[k] == rep1[k], k
     h = parity.make_handle(fl)
     with pytest.raises(binding.GoodRouteError) as e:
         h.gr_set_blend(0.5)                       # nothing observed yet
@@ -216,13 +157,6 @@ def test_tiny_fleet_with_queue_heavy_caps():
     for cap in (1, 7, 64, 103, 104, 105):
         fl.batch_cap = np.full(fl.n_inst, cap, dtype=np.int32)
         report(f"tiny cap {cap}", parity.run_and_check(fl))
-
-
-def test_heavy_fleet_with_batch_caps_sampled():
-    fl = workloads.make_fleet(workloads.spec("heavy", n_incoming=65536))
-    fl.batch_cap = workloads.batch_caps(fl, 0.8, 1.1, seed=3)
-    rep = parity.run_and_check(fl, sample=1024)
-    report("heavy caps", rep)
 
 
 def test_feedback_routing_with_batch_caps_request_by_request():

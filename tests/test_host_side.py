@@ -82,3 +82,70 @@ def test_classifier_accepts_reference_and_rejects_wrong_answers():
     assert np.all(ref2.inst != ex)
     want2, _, adm3, _ = parity.classify_choices(T, D, sim.rank, ex, ref2.inst.astype(np.int64))
     assert np.array_equal(want2, ref2.inst) and adm3.all()
+
+
+def _verdicts_from_matrix(sim, c0, ln, D, ex, hits, picked):
+    T = sim.pair_T(c0, ln, hits=hits)
+    return parity.classify_choices(T, D, sim.rank, ex, picked)
+
+
+def test_band_summary_agrees_with_the_matrix_classifier():
+    """The per-request summary the C reference gives for batches of any size leads to the same
+    verdicts (decided or not, acceptable or not, fallback bit) as the [n, M] classifier, for the
+    reference's own answers, for wrong ones, with exclusions and with cached prefixes."""
+    rng = np.random.default_rng(5)
+    for scale, seed in ((1.0, 1), (2.0, 2), (8.0, 3)):
+        fl = workloads.make_fleet(workloads.spec("mid", slo_scale=scale, occupancy_jitter=True, seed=seed))
+        sim = oracle.simulate(fl)
+        c0, ln, D = fl.in_prompt, fl.in_len, fl.in_budget.astype(np.float64)
+        # deadlines moved onto the boundary of some pair so that the band is populated
+        T = sim.pair_T(c0, ln)
+        rows = rng.choice(len(D), 600, replace=False)
+        D[rows] = T[rows, rng.integers(0, fl.n_inst, 600)] * (1 + rng.uniform(-2e-4, 2e-4, 600))
+        hits = workloads.cached_prefixes(fl, mean_hits=2.0, seed=seed)
+        ex = rng.integers(-1, fl.n_inst, len(D)).astype(np.int32)
+        for use_ex, use_hits in ((None, None), (ex, None), (None, hits), (ex, hits)):
+            ref = sim.route(c0, ln, D, exclude=use_ex, hits=use_hits)
+            for picked in (ref.inst.astype(np.int64), (ref.inst.astype(np.int64) + 1) % fl.n_inst,
+                           rng.integers(0, fl.n_inst, len(D)).astype(np.int64)):
+                want, robust, adm, fbk = _verdicts_from_matrix(sim, c0, ln, D, use_ex, use_hits, picked)
+                band = sim.band(c0, ln, D, picked, parity.EPS, exclude=use_ex, hits=use_hits)
+                r2, a2, f2 = parity.judge_with_band(band, D, sim.rank, picked)
+                assert np.array_equal(want, ref.inst)
+                assert np.array_equal(robust, r2) and np.array_equal(adm, a2) and np.array_equal(fbk, f2)
+                allowed = np.ones_like(T, dtype=bool)
+                if use_ex is not None:
+                    allowed[np.flatnonzero(use_ex >= 0), use_ex[use_ex >= 0]] = False
+                Th = sim.pair_T(c0, ln, hits=use_hits)
+                assert np.array_equal(band.picked_T, np.where(allowed[np.arange(len(D)), picked],
+                                                              Th[np.arange(len(D)), picked], np.inf))
+                assert np.array_equal(band.tmin, np.where(allowed, Th, np.inf).min(axis=1))
+            assert 0 < (~r2).sum() < 0.2 * len(D)
+
+
+def test_exact_ties_are_decided_and_go_to_the_lowest_index():
+    """Two different instances with the same latency bit for bit: the fallback choice is the one
+    with the lower index, and the classifiers call it decided (nothing else is acceptable)."""
+    from tests.fleets import two_equal_minima_in_one_lane
+    fl = two_equal_minima_in_one_lane()
+    sim = oracle.simulate(fl)
+    M = fl.n_inst if hasattr(fl, "n_inst") else len(fl.inst_class)
+    c0, ln, D = fl.in_prompt, fl.in_len, fl.in_budget.astype(np.float64)
+    assert sim.d[0] == 0.25 and sim.d[M - 1] == 0.5 and np.all(sim.d[1:M - 1] == 0.375)
+    assert sim.rank[M - 1] == 0 and sim.rank[0] == M - 1          # 64 positions apart
+    T = sim.pair_T(c0, ln)
+    tie = ln == 8
+    assert np.array_equal(T[tie, 0], T[tie, M - 1]) and np.all(T[tie, 0] == 4.0 + c0[tie] / 1024.0)
+    assert np.all(T[:, 1:M - 1] > np.maximum(T[:, 0], T[:, M - 1])[:, None])
+    ref = sim.route(c0, ln, D)
+    tight = D < 1.0
+    assert np.all(ref.inst[tight & tie] == 0)                     # equal T: lowest index
+    assert np.all(ref.inst[tight & (ln < 8)] == M - 1) and np.all(ref.inst[tight & (ln > 8)] == 0)
+    assert np.all(ref.inst[~tight] == M - 1) and np.all(ref.fallback == tight)
+    for picked, fine in ((ref.inst.astype(np.int64), True), (np.full(len(D), M - 1, dtype=np.int64), False)):
+        band = sim.band(c0, ln, D, picked, parity.EPS)
+        robust, adm, _ = parity.judge_with_band(band, D, sim.rank, picked)
+        want, robust_m, adm_m, _ = parity.classify_choices(T, D, sim.rank, None, picked)
+        assert robust.all() and robust_m.all() and np.array_equal(want, ref.inst)
+        assert np.all(band.equal[tie] == 2) and np.all(band.equal[~tie] == 1)
+        assert fine == bool(np.all(picked[tight & tie] == want[tight & tie]))
