@@ -150,6 +150,28 @@ int gr_score_route(gr_fleet* f, int64_t n_req,
                    float* out_T, void* hip_stream);
 
 /*
+ * gr_score_route for callers that cannot allocate device memory or call anything that might:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid it.  Same inputs,
+ * outputs and answers as gr_score_route's pair-by-pair pass (a thread per (request, instance)
+ * pair, whatever gr_set_small_batch_pairs says; no out_T), for at most
+ * GR_NOALLOC_MAX_REQUESTS requests per call; more is GR_ERR_TOO_LARGE.  The running
+ * selections of the pass (16 bytes per request) live in a fixed array of 64 KiB in the
+ * library's device image instead of the handle's workspace; the call queues three kernels on
+ * the stream (one sets the array's slots for this batch) and calls no hipMalloc, hipFree,
+ * memset, copy or synchronisation.  Every GPU holds one such array for the life of the
+ * process and every call on that GPU uses it, whatever the handle: calls that overlap on one
+ * GPU (two streams, two threads, two handles) race and must be serialised by the caller.
+ * The handle must have been created on the current device (the array's address is looked up
+ * once per device, in gr_create).
+ */
+#define GR_NOALLOC_MAX_REQUESTS 4096
+int gr_score_route_noalloc(gr_fleet* f, int64_t n_req,
+                           const int32_t* ctx0, const int32_t* pred_len, const float* budget,
+                           const int32_t* exclude_inst,
+                           int32_t* out_inst, float* out_slack, uint8_t* out_fallback,
+                           void* hip_stream);
+
+/*
  * Step 2 with cached prefixes (Eq. 2's hit prefix token length H_{r,g};
  * Alg. 1's prefix-reuse lookup before T(r,g) is formed).  As gr_score_route,
  * but request r already has hit_len[k] of its ctx0 tokens cached on instance

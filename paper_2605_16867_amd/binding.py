@@ -12,7 +12,7 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "csrc", "libgoodroute.so")
 
-EXPORTS = ("gr_create", "gr_destroy", "gr_build_status", "gr_score_route", "gr_score_route_cached", "gr_route_feedback",
+EXPORTS = ("gr_create", "gr_destroy", "gr_build_status", "gr_score_route", "gr_score_route_noalloc", "gr_score_route_cached", "gr_route_feedback",
            "gr_risk_scan", "gr_observe", "gr_set_blend", "gr_set_batch_cap", "gr_set_small_batch_pairs",
            "gr_device_status", "gr_strerror", "gr_profile_enable", "gr_profile_select", "gr_profile_read",
            "gr_profile_kernel_count", "gr_profile_kernel_name")
@@ -42,6 +42,8 @@ def lib() -> C.CDLL:
         l.gr_build_status.argtypes = [p, p, p, p, p, i64, p, p, p, i64, p, p, p, p, p]
         l.gr_score_route.restype = C.c_int
         l.gr_score_route.argtypes = [p, i64, p, p, p, p, p, p, p, p, p]
+        l.gr_score_route_noalloc.restype = C.c_int
+        l.gr_score_route_noalloc.argtypes = [p, i64, p, p, p, p, p, p, p, p]
         l.gr_score_route_cached.restype = C.c_int
         l.gr_score_route_cached.argtypes = [p, i64, p, p, p, p, p, p, p, i64, p, p, p, p, p]
         l.gr_route_feedback.restype = C.c_int
@@ -150,6 +152,17 @@ class Fleet:
             _dev(out_inst, i32, "out_inst", n), _dev(out_slack, f32, "out_slack", n),
             _dev(out_fallback, torch.uint8, "out_fallback", n),
             _dev(out_T, f32, "out_T", n * self.n_inst), _stream()), "gr_score_route")
+
+    def gr_score_route_noalloc(self, ctx0, pred_len, budget, out_inst, out_slack, exclude_inst=None,
+                               out_fallback=None) -> None:
+        import torch
+        i32, f32 = torch.int32, torch.float32
+        n = ctx0.numel()
+        _check(lib().gr_score_route_noalloc(
+            self._h, n, _dev(ctx0, i32, "ctx0"), _dev(pred_len, i32, "pred_len", n),
+            _dev(budget, f32, "budget", n), _dev(exclude_inst, i32, "exclude_inst", n),
+            _dev(out_inst, i32, "out_inst", n), _dev(out_slack, f32, "out_slack", n),
+            _dev(out_fallback, torch.uint8, "out_fallback", n), _stream()), "gr_score_route_noalloc")
 
     def gr_score_route_cached(self, ctx0, pred_len, budget, hit_off, hit_inst, hit_len, out_inst, out_slack,
                               exclude_inst=None, out_fallback=None, out_T=None) -> None:

@@ -115,6 +115,11 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         return GR_ERR_HIP;
     }
     if (score_prepare(f) != GR_OK) { gr_destroy(f); return GR_ERR_HIP; }
+    {   // the address of the fixed scratch array on this device, for gr_score_route_noalloc
+        unsigned long long* unused = nullptr;
+        const int rc = static_scratch(f->device, &unused);
+        if (rc != GR_OK && rc != GR_ERR_TOO_LARGE) { gr_destroy(f); return rc; }
+    }
     *out = f;
     return GR_OK;
 }
@@ -182,6 +187,23 @@ int gr_score_route(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_
 {
     return score_route(f, n_req, ctx0, pred_len, budget, exclude_inst, out_inst, out_slack, out_fallback, out_T,
                        hip_stream, true);
+}
+
+int gr_score_route_noalloc(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_t* pred_len,
+                           const float* budget, const int32_t* exclude_inst, int32_t* out_inst,
+                           float* out_slack, uint8_t* out_fallback, void* hip_stream)
+{
+    if (!f || n_req < 0) return GR_ERR_INVALID_ARG;
+    if (n_req > GR_NOALLOC_MAX_REQUESTS) return GR_ERR_TOO_LARGE;
+    if (!f->has_status) return GR_ERR_NO_STATUS;
+    if (n_req == 0) return GR_OK;
+    if (!ctx0 || !pred_len || !budget || !out_inst || !out_slack) return GR_ERR_INVALID_ARG;
+    ReqSrc src{};
+    src.ctx0 = ctx0; src.pred_len = pred_len; src.budget = budget; src.exclude = exclude_inst;
+    src.n = n_req;
+    ScoreOut o{};
+    o.inst = out_inst; o.slack = out_slack; o.fallback = out_fallback;
+    return launch_score_static(f, src, o, static_cast<hipStream_t>(hip_stream));
 }
 
 int gr_score_route_cached(gr_fleet* f, int64_t n_req, const int32_t* ctx0, const int32_t* pred_len,

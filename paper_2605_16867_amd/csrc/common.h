@@ -195,6 +195,8 @@ size_t score_lds_bytes(const gr_fleet* f);
 int score_prepare(gr_fleet* f);
 int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& out, hipStream_t s,
                  bool small_batch_ok = false);
+int static_scratch(int device, unsigned long long** out);
+int launch_score_static(gr_fleet* f, const ReqSrc& src, const ScoreOut& out, hipStream_t s);
 int launch_hits(gr_fleet* f, const ReqSrc& src, const int* hit_off, const int* hit_inst, const int* hit_len,
                 int64_t n_hits, const ScoreOut& out, hipStream_t s);
 

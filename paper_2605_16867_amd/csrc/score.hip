@@ -19,8 +19,15 @@
 // A batch of a few requests skips grouping and table: a thread per pair with
 // its own binary search (k_direct).
 #include <cfloat>
+#include <mutex>
 
 #include "common.h"
+
+// The running selections of the pair-by-pair pass for callers that may not allocate: a fixed
+// array in the library's own device image (each GPU the library runs on holds a copy of it
+// until the process ends).  Host code never uses this name as an address: it asks the runtime
+// for the array's address on the current device once (static_scratch below) and passes that.
+static __device__ __align__(256) unsigned long long scratch[2 * gr::kDirectMax];
 
 namespace gr {
 namespace {
@@ -1093,6 +1100,7 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
         const float* __restrict__ pe = rv.E + half * kWave + lw;
         const float2* __restrict__ pk = rv.posK + half * kWave + lw;
         float blk = (float)half, key = 0x1p100f;
+        float back = (float)(rv.nblk - half), keyL = 0x1p100f;
 #pragma unroll 8
         for (int i = 0; i < rv.nblk / 2; ++i) {       // block 2 i + half
             const float Tc = fmaf(s_c0, kappa_of(pk[i * 2 * kWave], rv.Lf), pe[i * 2 * kWave]);
@@ -1100,21 +1108,20 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
             key = fminf(key, fmaf(off, 0x1p100f, blk));
             keyL = fminf(keyL, fmaf(off, 0x1p100f, back));
             blk += 2.0f;
+            back -= 2.0f;
         }
         if (key < 0x1p30f) { firstB = (int)key; lastB = rv.nblk - (int)keyL; }
-        float back = (float)(rv.nblk - half), keyL = 0x1p100f;
     }
     firstB = min(firstB, __shfl_xor(firstB, 32, kWave));
+    lastB = max(lastB, __shfl_xor(lastB, 32, kWave));
     const int candP = firstB < rv.nblk ? firstB * kWave + (win & (kWave - 1)) : -1;
     // equal minima (in several lanes, or at several positions of one) and a minimum on the
     // excluded instance: one by one
     const bool slow = mine && (foundP >= 0 ? foundP == rec.pex
-            back -= 2.0f;
                                            : (win == kWave || candP < 0 || candP == rec.pex || lastB != firstB));
 
     int p = foundP >= 0 ? foundP : candP;
     float T = foundP >= 0 ? foundT : Tm;
-    lastB = max(lastB, __shfl_xor(lastB, 32, kWave));
     bool found = foundP >= 0;
 
     unsigned long long redo = __ballot(slow);
@@ -1326,6 +1333,20 @@ __global__ __launch_bounds__(kBlock) void k_direct_finish(DirectArgs a)
 
 __global__ void k_set_int(int* p, int v) { *p = v; }
 
+// all ones = "no selection yet", for the first n requests of both halves
+__global__ __launch_bounds__(kBlock) void k_fill_ones(unsigned long long* __restrict__ best, int n)
+{
+    const int i = blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) {
+        best[i] = ~0ull;
+        best[kDirectMax + i] = ~0ull;
+    }
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+unsigned long long* scratch_ptr[kMaxDevices];      // the array's address on each device, once asked for
+
 template <typename K>
 bool set_lds(K kernel, size_t bytes)
 {
@@ -1357,6 +1378,60 @@ int score_prepare(gr_fleet* f)
     return ok ? GR_OK : GR_ERR_HIP;
 }
 
+// Alg. 1 pair by pair for up to kDirectMax requests; `best`: 2 * kDirectMax running selections,
+// all ones on entry for the requests of this batch, and left so.
+static int launch_direct(gr_fleet* f, const ReqSrc& src, const ScoreOut& out, unsigned long long* best, hipStream_t s)
+{
+    const int64_t n = src.n;
+    DirectArgs d{};
+    d.ctx0 = src.ctx0; d.pred_len = src.pred_len; d.budget = src.budget; d.exclude = src.exclude;
+    d.order = f->order; d.hN = f->hN; d.cls = f->cls; d.inst_class = f->inst_class;
+    d.tabR = f->tabR; d.tabGH = f->tabGH; d.headGH = f->headGH; d.posK = f->posK;
+    d.best_feasible = best; d.best_any = best + kDirectMax;
+    d.out_inst = out.inst; d.out_slack = out.slack; d.out_fallback = out.fallback; d.out_T = out.T;
+    d.n = (int)n; d.n_inst = f->n_inst; d.m_pad = f->m_pad; d.cap = f->cap; d.max_len = f->max_len;
+    d.keep = (float)(1.0 - f->lam_built);
+    {
+        ProfScope ps(f, kDirect, s);
+        hipLaunchKernelGGL(k_direct, dim3((f->m_pad + kBlock - 1) / kBlock, (unsigned)n), dim3(kBlock), 0, s, d);
+    }
+    {
+        ProfScope ps(f, kDirectFinish, s);
+        hipLaunchKernelGGL(k_direct_finish, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, d);
+    }
+    return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
+}
+
+int static_scratch(int device, unsigned long long** out)
+{
+    if (device < 0 || device >= kMaxDevices) return GR_ERR_TOO_LARGE;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[device]) {
+        int current = -1;
+        if (hipGetDevice(&current) != hipSuccess || current != device) return GR_ERR_INVALID_ARG;
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GR_ERR_HIP;
+        scratch_ptr[device] = static_cast<unsigned long long*>(p);
+    }
+    *out = scratch_ptr[device];
+    return GR_OK;
+}
+
+int launch_score_static(gr_fleet* f, const ReqSrc& src, const ScoreOut& out, hipStream_t s)
+{
+    if (src.n == 0) return GR_OK;
+    if (src.n > kDirectMax) return GR_ERR_TOO_LARGE;
+    unsigned long long* best = nullptr;
+    const int rc = static_scratch(f->device, &best);
+    if (rc != GR_OK) return rc;
+    // the array keeps whatever the last call on this GPU left (a call that was cut short may
+    // have left selections behind): set this batch's slots before use, with a kernel, so that
+    // the call can be recorded into a graph
+    hipLaunchKernelGGL(k_fill_ones, dim3((unsigned)((src.n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, best, (int)src.n);
+    if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
+    return launch_direct(f, src, out, best, s);
+}
+
 int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& out, hipStream_t s,
                  bool small_batch_ok)
 {
@@ -1367,25 +1442,8 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     }
     // up to about two million pairs (the default) a thread per pair is cheaper than the five kernels
     // of the grouped pass
-    if (small_batch_ok && !migrate && n <= kDirectMax && n * f->m_pad <= f->small_batch_pairs) {
-        DirectArgs d{};
-        d.ctx0 = src.ctx0; d.pred_len = src.pred_len; d.budget = src.budget; d.exclude = src.exclude;
-        d.order = f->order; d.hN = f->hN; d.cls = f->cls; d.inst_class = f->inst_class;
-        d.tabR = f->tabR; d.tabGH = f->tabGH; d.headGH = f->headGH; d.posK = f->posK;
-        d.best_feasible = f->direct_best; d.best_any = f->direct_best + kDirectMax;
-        d.out_inst = out.inst; d.out_slack = out.slack; d.out_fallback = out.fallback; d.out_T = out.T;
-        d.n = (int)n; d.n_inst = f->n_inst; d.m_pad = f->m_pad; d.cap = f->cap; d.max_len = f->max_len;
-        d.keep = (float)(1.0 - f->lam_built);
-        {
-            ProfScope ps(f, kDirect, s);
-            hipLaunchKernelGGL(k_direct, dim3((f->m_pad + kBlock - 1) / kBlock, (unsigned)n), dim3(kBlock), 0, s, d);
-        }
-        {
-            ProfScope ps(f, kDirectFinish, s);
-            hipLaunchKernelGGL(k_direct_finish, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, d);
-        }
-        return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
-    }
+    if (small_batch_ok && !migrate && n <= kDirectMax && n * f->m_pad <= f->small_batch_pairs)
+        return launch_direct(f, src, out, f->direct_best, s);
     const int bins = f->bins;
     // requests per workgroup of the grouping kernels.  Every workgroup pays a pass over all length
     // bins and one global atomic per length it has seen: the histogram of a large batch is faster
