@@ -1,5 +1,5 @@
 // Status build (step 1 of the path): per instance, a sort of the remaining
-// lengths, three integer prefix sums over the sorted order, and from them the
+// lengths, three exact prefix sums over the sorted order, and from them the
 // finish time of every held request (Sec. 3.4's "expected finish time"), q_g
 // and d_g of Eq. 2, and the instance table used for scoring; then the
 // capability order of Alg. 1's argmax d_g.
@@ -153,10 +153,10 @@ constexpr int kBuildWaves = kBlock / kWave;
 
 constexpr int log2_of(int v) { return v <= 1 ? 0 : 1 + log2_of(v / 2); }
 
-// (up to 8 sort words per lane the kernel is held to 128 registers, four waves per SIMD: a fleet
-// of 4 096 instances is then resident at once)
-template <int kEPL, bool kCapAware>
-__global__ __launch_bounds__(kBlock, (kEPL <= 8 && !kCapAware ? 4 : 1)) void k_build(BuildArgs a)
+// The build under batch caps (a kernel of its own: the event loop's registers would cost the
+// plain build, k_build_lean below, a wave per SIMD).
+template <int kEPL>
+__global__ __launch_bounds__(kBlock, 1) void k_build_capped(BuildArgs a)
 {
     extern __shared__ uint32_t smem[];
     constexpr int kCap = kWave * kEPL;
@@ -255,9 +255,8 @@ __global__ __launch_bounds__(kBlock, (kEPL <= 8 && !kCapAware ? 4 : 1)) void k_b
     // has room now, a newcomer is admitted now (q_g = now, and the closed form below is built on
     // what is running); if not, it is admitted after the departure that makes room, which the
     // closed form itself gives (further down).
-    // (kCapAware is a kernel of its own: the event loop's registers would cost the plain build a wave per SIMD)
-    const int cap_g = kCapAware ? max(a.batch_cap[g], 1) : 0x7fffffff;
-    const bool capped = kCapAware && cap_g <= N;
+    const int cap_g = max(a.batch_cap[g], 1);
+    const bool capped = cap_g <= N;
     int Nrun = N;
     double d_first = -1.0;
     if (capped) {
@@ -364,7 +363,7 @@ __global__ __launch_bounds__(kBlock, (kEPL <= 8 && !kCapAware ? 4 : 1)) void k_b
     // With R' = R - s, c' = c + s over the survivors (positions vstar.. of the sorted order):
     //   sum R' = sum R - m s,   sum (c' R' + tri(R')) = sum (c R + tri(R)) - s sum c - m tri(s),
     //   sum c' = sum c + m s    (m terms each; all integers, exact)
-    if constexpr (kCapAware) {
+    {
         if (capped && Nrun >= cap_g) {
             const int kstar = Nrun - cap_g + 1;
             long long Y1 = Y, X1 = X, P1 = Pc;
@@ -511,6 +510,266 @@ __global__ __launch_bounds__(kBlock, (kEPL <= 8 && !kCapAware ? 4 : 1)) void k_b
     }
 }
 
+// ---- the build without batch caps: the same results from fewer instructions.
+//
+// The instance's running requests are read and their results written through buffer
+// descriptors that span exactly the instance's slice of the caller's arrays: an offset past
+// the slice reads zero and stores nothing, so there is no address arithmetic and no branch per
+// entry.  The three prefix sums run in double precision (every term and every sum is an
+// integer below 2^53, so they are exact), first along the lane's own consecutive positions,
+// then across the lanes by DPP shifts, and the table and finish times come out of them with
+// fused multiply-adds, without any integer-to-double conversion of a 64-bit sum.
+
+// x of the lane `ctrl` names (0.0 where there is none or the row is masked out), both halves
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ double dpp_or_zero(double x)
+{
+    const long long b = __builtin_bit_cast(long long, x);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)b, kCtrl, kRowMask, 0xf, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), kCtrl, kRowMask, 0xf, false);
+    return __builtin_bit_cast(double, ((long long)hi << 32) | (unsigned)lo);
+}
+
+// Inclusive prefix sum over the lanes of a wave (see wave_incl_scan_i32 for the pattern).
+__device__ __forceinline__ double wave_incl_scan_f64(double v)
+{
+    v += dpp_or_zero<0x111, 0xf>(v);   // row_shr:1
+    v += dpp_or_zero<0x112, 0xf>(v);   // row_shr:2
+    v += dpp_or_zero<0x114, 0xf>(v);   // row_shr:4
+    v += dpp_or_zero<0x118, 0xf>(v);   // row_shr:8
+    v += dpp_or_zero<0x142, 0xa>(v);   // row_bcast:15 into rows 1, 3
+    v += dpp_or_zero<0x143, 0xc>(v);   // row_bcast:31 into rows 2, 3
+    return v;
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int lane)
+{
+    const long long b = __builtin_bit_cast(long long, v);
+    const int lo = __builtin_amdgcn_readlane((int)b, lane), hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
+    return __builtin_bit_cast(double, ((long long)hi << 32) | (unsigned)lo);
+}
+
+constexpr int kBufferDwords = 0x00020000;   // descriptor word 3: raw buffer of 32-bit elements
+
+template <int kEPL>
+__global__ __launch_bounds__(kBlock, (kEPL <= 8 ? 4 : 1)) void k_build_lean(BuildArgs a)
+{
+    extern __shared__ uint32_t smem[];
+    constexpr int kCap = kWave * kEPL;
+    constexpr int kIdxBits = log2_of(kCap);
+    constexpr uint32_t kIdxMask = (1u << kIdxBits) - 1u;
+    const int lane = lane_id();
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int g = blockIdx.x * kBuildWaves + wave;        // wave-uniform: what follows is scalar
+    if (g >= a.n_inst) return;
+    {   // feedback routing: an instance that has been given nothing since its table was built keeps it
+        const bool touched = a.pend_touched[g] != 0;
+        if (lane == 0 && touched) a.pend_touched[g] = 0;
+        if (a.only_touched && !touched) {
+            if (lane == 0) a.rank_acc[g] = 0;
+            return;
+        }
+    }
+    int* ctx = reinterpret_cast<int*>(smem) + wave * kCap;      // this wave's contexts, by entry index
+
+    const ClassCoef cc = a.cls[a.inst_class[g]];
+    // offsets are clamped into the arrays, so broken CSR data cannot index outside them
+    const int a0 = (int)min((int64_t)max(a.act_off[g], 0), a.n_active);
+    const int q0 = (int)min((int64_t)max(a.q_off[g], 0), a.n_queued);
+    int A = (int)max(min((int64_t)a.act_off[g + 1], a.n_active) - a0, (int64_t)0);
+    int Q = (int)max(min((int64_t)a.q_off[g + 1], a.n_queued) - q0, (int64_t)0);
+    int status = 0;
+    if (A > a.max_entries) { A = a.max_entries; status |= GR_DEV_ENTRIES_DROPPED; }
+    if (Q > a.max_entries - A) { Q = a.max_entries - A; status |= GR_DEV_ENTRIES_DROPPED; }
+    int P = a.use_pending ? min(a.pend_cnt[g], kCap) : 0;
+    if (P > a.max_entries - A - Q) { P = a.max_entries - A - Q; status |= GR_DEV_ENTRIES_DROPPED; }
+    const int N = A + Q + P;
+
+    // the instance's slice of each array of running requests (A entries from a0 on)
+    const auto slice = [&](const void* base, size_t elem) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(static_cast<const char*>(base)) + (size_t)a0 * elem,
+                                                 0, A * (int)elem, kBufferDwords);
+    };
+    const __amdgpu_buffer_rsrc_t b_rem = slice(a.act_rem, 4), b_prompt = slice(a.act_prompt, 4),
+                                 b_gen = slice(a.act_gen, 4);
+
+    // load, entry i = 64 r + lane: all loads in flight together
+    const int lane4 = lane * 4;
+    int rem_in[kEPL], c_in[kEPL], gen_in[kEPL];
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) {
+        rem_in[r] = __builtin_amdgcn_raw_buffer_load_b32(b_rem, lane4, r * kWave * 4, 0);
+        c_in[r] = __builtin_amdgcn_raw_buffer_load_b32(b_prompt, lane4, r * kWave * 4, 0);
+        gen_in[r] = __builtin_amdgcn_raw_buffer_load_b32(b_gen, lane4, r * kWave * 4, 0);
+    }
+    long long qsum = 0;
+    if (Q + P > 0) {     // queued requests, and those routed since the status (feedback routing)
+        const int* pp = a.pend_prompt + (size_t)g * kCap;
+        const int* pl = a.pend_len + (size_t)g * kCap;
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r) {
+            const int i = r * kWave + lane;
+            if (i >= A && i < N) {
+                const bool queued = i < A + Q;
+                rem_in[r] = queued ? a.q_len[q0 + i - A] : pl[i - A - Q];
+                c_in[r] = queued ? a.q_prompt[q0 + i - A] : pp[i - A - Q];
+                qsum += c_in[r];
+            }
+        }
+        qsum = wave_sum(qsum);
+    }
+    const double q = cc.delta * (double)qsum;
+
+    // one sort word per entry = (remaining length << kIdxBits) | i; past the last entry all ones
+    uint32_t key[kEPL];
+    bool bad = false;
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) {
+        const int i = r * kWave + lane;
+        const int rem = min(max(rem_in[r], 0), a.max_len);
+        bad |= rem != rem_in[r];
+        key[r] = i < N ? ((uint32_t)rem << kIdxBits) | (uint32_t)i : 0xFFFFFFFFu;
+        ctx[i] = c_in[r] + gen_in[r];          // (zero past the last entry: the loads returned zeros)
+    }
+    if (__ballot(bad)) status |= GR_DEV_LEN_CLAMPED;
+    if (status && lane == 0) atomicOr(&a.counters[0], status);
+    if (a.act_budget) {      // the instance of each running request, for the migration pass of a risk scan
+        const __amdgpu_buffer_rsrc_t b_inst = slice(a.act_inst, 4);
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r) __builtin_amdgcn_raw_buffer_store_b32(g, b_inst, lane4, r * kWave * 4, 0);
+    }
+
+    bitonic_sort<kEPL>(key, lane);
+
+    // the wave's own LDS writes above must be visible to its reads below
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // sorted position v = lane * kEPL + r; per lane the sums of R, c*R + tri(R), c
+    int idx[kEPL], Ri[kEPL], ci[kEPL];
+    const int mine = N - lane * kEPL;            // positions of this lane that hold an entry
+    // an entry's terms of the three sums, as doubles (formed twice, here and below, rather than kept)
+    const auto terms = [&](int r, double& Rd, double& cd, double& td, double& xe) {
+        Rd = (double)Ri[r];
+        cd = (double)ci[r];
+        td = (double)(Ri[r] * (Ri[r] - 1) / 2);
+        xe = fma(cd, Rd, td);
+    };
+    double yl = 0.0, xl = 0.0, cl = 0.0;
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) {
+        idx[r] = (int)(key[r] & kIdxMask);
+        Ri[r] = r < mine ? (int)(key[r] >> kIdxBits) : 0;
+        // (a position without an entry carries index kCap - 1, an entry that does not exist either: zero)
+        ci[r] = ctx[idx[r]];
+    }
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) {
+        double Rd, cd, td, xe;
+        terms(r, Rd, cd, td, xe);
+        yl += Rd; xl += xe; cl += cd;
+    }
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) asm volatile("" : "+v"(Ri[r]), "+v"(ci[r]));   // (so that the terms are not kept in registers)
+    const double yi = wave_incl_scan_f64(yl), xi = wave_incl_scan_f64(xl), pi = wave_incl_scan_f64(cl);
+    const double Ctot = readlane_f64(pi, kWave - 1);
+    double Y = yi - yl, X = xi - xl, Pc = pi - cl;
+
+    // with a blend, every estimate below is keep * (white-box value) + lam * (Eq. 2 with the smoothed status)
+    const bool blended = a.lam != 0.0;
+    const double keep = 1.0 - a.lam;
+    const double bq = blended ? a.emaQ[g] : 0.0, bp = blended ? a.emaP[g] : 0.0, bd = blended ? a.emaD[g] : 0.0;
+
+    // table entry v describes the segment after the v+1 shortest requests, n of them still running:
+    //   E_g(L) = Gq + L * H + tri(L) * gamma * (n + 1)
+    //   Gq = q + beta * Y + gamma * X,   H = alpha + beta * (n + 1) + gamma * S
+    // and the request at position v finishes at q + alpha R + beta (Y + n R) + gamma (X + R S + n tri(R)).
+    const __amdgpu_buffer_rsrc_t b_fin = slice(a.out_act_finish, 4);
+    __amdgpu_buffer_rsrc_t b_bud = b_fin, b_flag = b_fin;
+    if (a.act_budget) { b_bud = slice(a.act_budget, 4); b_flag = slice(a.out_flag, 1); }
+    uint16_t tR[kEPL];
+    float2 tGH[kEPL];
+    float fin32[kEPL], bud[kEPL];
+    unsigned late = 0;                           // bit r: the request at position r finishes after its budget
+    if (a.act_budget) {
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r) bud[r] = __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(b_bud, idx[r] * 4, 0, 0));
+    }
+    double n_here = (double)mine;                // requests still running from this position on, itself included
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r) {
+        double Rd, cd, td, xe;
+        terms(r, Rd, cd, td, xe);
+        Y += Rd; X += xe; Pc += cd;
+        const double n_after = n_here - 1.0, S_next = Ctot - Pc;
+        double Gq = fma(cc.gamma, X, fma(cc.beta, Y, q));
+        double Hs = fma(cc.gamma, S_next, fma(cc.beta, n_here, cc.alpha));
+        double fin = fma(cc.gamma, fma(n_after, td, fma(Rd, S_next, X)),
+                         fma(cc.beta, fma(n_after, Rd, Y), fma(cc.alpha, Rd, q)));
+        n_here = n_after;
+        if (blended) {
+            Gq = keep * Gq + a.lam * bq;
+            Hs = keep * Hs + a.lam * bd;
+            // black-box finish: d per remaining token; a queued request also waits and prefills
+            fin = keep * fin + a.lam * (idx[r] < A ? bd * Rd : (bq + bp * cd) + bd * Rd);
+        }
+        fin32[r] = (float)fin;
+        if (a.act_budget) late |= (unsigned)(fin > (double)bud[r]) << r;     // decided in double precision
+        tR[r] = r < mine ? (uint16_t)Ri[r] : (uint16_t)0xFFFFu;
+        tGH[r] = make_float2((float)Gq, (float)Hs);
+    }
+    // (a position without an entry carries index kCap - 1 >= N: past the slice, nothing is stored)
+#pragma unroll
+    for (int r = 0; r < kEPL; ++r)
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_int(fin32[r]), b_fin, idx[r] * 4, 0, 0);
+    if (a.act_budget) {
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r)
+            __builtin_amdgcn_raw_buffer_store_b8((unsigned char)((late >> r) & 1u), b_flag, idx[r], 0, 0);
+    }
+    if (Q > 0 && a.out_q_finish) {
+#pragma unroll
+        for (int r = 0; r < kEPL; ++r)
+            if (r < mine && idx[r] >= A && idx[r] < A + Q) a.out_q_finish[q0 + idx[r] - A] = fin32[r];
+    }
+    {
+        uint16_t* dstR = a.tabR + (size_t)g * kCap + lane * kEPL;
+        float2* dstGH = a.tabGH + (size_t)g * kCap + lane * kEPL;
+        if constexpr (kEPL >= 8) {
+#pragma unroll
+            for (int r = 0; r < kEPL; r += 8) {
+                uint4 w;
+                w.x = tR[r] | ((uint32_t)tR[r + 1] << 16); w.y = tR[r + 2] | ((uint32_t)tR[r + 3] << 16);
+                w.z = tR[r + 4] | ((uint32_t)tR[r + 5] << 16); w.w = tR[r + 6] | ((uint32_t)tR[r + 7] << 16);
+                *reinterpret_cast<uint4*>(dstR + r) = w;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < kEPL; ++r) dstR[r] = tR[r];
+        }
+        if constexpr (kEPL >= 2) {
+#pragma unroll
+            for (int r = 0; r < kEPL; r += 2)
+                *reinterpret_cast<float4*>(dstGH + r) = make_float4(tGH[r].x, tGH[r].y, tGH[r + 1].x, tGH[r + 1].y);
+        } else {
+            dstGH[0] = tGH[0];
+        }
+    }
+    if (lane == 0) {
+        double Gq0 = q, H0 = fma(cc.gamma, Ctot, fma(cc.beta, (double)(N + 1), cc.alpha));
+        if (blended) { Gq0 = keep * Gq0 + a.lam * bq; H0 = keep * H0 + a.lam * bd; }
+        a.headGH[g] = make_float2((float)Gq0, (float)H0);
+        a.hN[g] = N;
+        a.rank_acc[g] = 0;
+        if (!a.use_pending) a.pend_cnt[g] = 0;
+        double d = fma(cc.gamma, Ctot, fma(cc.beta, (double)N, cc.alpha));     // the next decode step
+        if (blended) d = keep * d + a.lam * bd;
+        a.hD[g] = d;
+        if (a.out_d) a.out_d[g] = d;
+    }
+}
+
 // Capability order of Alg. 1's argmax d_g: rank 0 = largest d_g, equal d_g by
 // index.  rank_g = #{h : d_h > d_g} + #{h < g : d_h = d_g}, counted over tiles of
 // 64 instances x 256 competitors and added up with atomics.
@@ -617,9 +876,9 @@ template <int kEPL>
 void launch_build(const BuildArgs& b, int M, hipStream_t s)
 {
     const dim3 grid((M + kBuildWaves - 1) / kBuildWaves);
-    const size_t lds = (size_t)kBuildWaves * 3 * kWave * kEPL * sizeof(int);
-    if (b.batch_cap) hipLaunchKernelGGL((k_build<kEPL, true>), grid, dim3(kBlock), lds, s, b);
-    else hipLaunchKernelGGL((k_build<kEPL, false>), grid, dim3(kBlock), lds, s, b);
+    const size_t lds = (size_t)kBuildWaves * kWave * kEPL * sizeof(int);
+    if (b.batch_cap) hipLaunchKernelGGL((k_build_capped<kEPL>), grid, dim3(kBlock), 3 * lds, s, b);
+    else hipLaunchKernelGGL((k_build_lean<kEPL>), grid, dim3(kBlock), lds, s, b);
 }
 
 }  // namespace
