@@ -157,7 +157,8 @@ int gr_score_route(gr_fleet* f, int64_t n_req,
  * GR_NOALLOC_MAX_REQUESTS requests per call; more is GR_ERR_TOO_LARGE.  The running
  * selections of the pass (16 bytes per request) live in a fixed array of 64 KiB in the
  * library's device image instead of the handle's workspace; the call queues three kernels on
- * the stream (one sets the array's slots for this batch) and calls no hipMalloc, hipFree,
+ * the stream (one sets the array's slots for this batch; two more, for the capability order,
+ * on the first scoring call after a status build) and calls no hipMalloc, hipFree,
  * memset, copy or synchronisation.  Every GPU holds one such array for the life of the
  * process and every call on that GPU uses it, whatever the handle: calls that overlap on one
  * GPU (two streams, two threads, two handles) race and must be serialised by the caller.

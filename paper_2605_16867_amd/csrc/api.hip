@@ -114,7 +114,7 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         gr_destroy(f);
         return GR_ERR_HIP;
     }
-    if (score_prepare(f) != GR_OK) { gr_destroy(f); return GR_ERR_HIP; }
+    if (score_prepare(f) != GR_OK || status_prepare() != GR_OK) { gr_destroy(f); return GR_ERR_HIP; }
     {   // the address of the fixed scratch array on this device, for gr_score_route_noalloc
         unsigned long long* unused = nullptr;
         const int rc = static_scratch(f->device, &unused);

@@ -159,6 +159,7 @@ struct gr_fleet {
     float* grp_min = nullptr;    // [m_pad / kMemoP][row_cap] least E of each run of kMemoP positions, per row
     float2* grp_k = nullptr;     // [m_pad / kMemoP] least delta and least gamma of each run
     bool tables_current = false;   // every instance's table is from the last inputs, blend weight and caps
+    bool ranks_current = false;    // rank, order and posK belong to the current d_g (else the next scoring pass makes them)
     int* pend_touched = nullptr;   // [M] 1: given requests since its table was built
     int64_t small_batch_pairs = int64_t(1) << 18;   // largest batch, in pairs, scored pair by pair
     unsigned long long* direct_best = nullptr;   // [2][kDirectMax] running selections of a small batch (all ones between calls)
@@ -185,7 +186,26 @@ struct ProfScope {
 };
 
 
+// What the two steps of the capability order need (Alg. 1's argmax d_g: rank 0 = largest d_g,
+// equal d_g by index).  They run as kernels of their own or as extra workgroups of the first two
+// kernels of a scoring pass (see launch_score).
+struct RankArgs {
+    const double* d;        // [M] d_g
+    int* rank_acc;          // [M] partial counts, zero before the count and again after the final step
+    const ClassCoef* cls;
+    const int* inst_class;
+    const double* emaP;
+    double lam;
+    int *rank, *order;
+    float2* posK;
+    int* out_rank;          // may be null
+    int n_inst, m_pad;
+};
+
 // status.hip
+int status_prepare();
+int launch_ranks(gr_fleet* f, int* out_rank, hipStream_t s);
+RankArgs rank_args(const gr_fleet* f, int* out_rank);
 int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s);
 int launch_commit(gr_fleet* f, int64_t n, const int* inst, const int* ctx0, const int* pred_len, hipStream_t s);
 int launch_ema(gr_fleet* f, double w, const float* s_q, const float* s_p, const float* s_d, hipStream_t s);
@@ -236,6 +256,49 @@ __device__ inline int wave_incl_scan_i32(int v)
     v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
     v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
     return v;
+}
+
+// rank_g = #{h : d_h > d_g} + #{h < g : d_h = d_g}, counted over tiles of 64 instances x kThreads
+// competitors (tile `bx` of the instances, tile `by` of the competitors) and added up with
+// atomics.  `comp`: kThreads doubles of LDS.  Every thread of the workgroup must call it.
+template <int kThreads>
+__device__ inline void rank_count_tile(const RankArgs& a, int bx, int by, double* comp)
+{
+    const int tid = threadIdx.x;
+    const int g = bx * kWave + (tid & (kWave - 1));
+    const int h0 = by * kThreads;
+    comp[tid] = h0 + tid < a.n_inst ? a.d[h0 + tid] : 0.0;
+    __syncthreads();
+    if (g >= a.n_inst) return;
+    const double dg = a.d[g];
+    const int part = tid / kWave;                 // which 64 of the competitors
+    const int lim = min(kWave, a.n_inst - h0 - part * kWave);
+    int r = 0;
+    for (int j = 0; j < lim; ++j) {
+        const double dh = comp[part * kWave + j];
+        r += (dh > dg) || (dh == dg && h0 + part * kWave + j < g);
+    }
+    if (r) atomicAdd(&a.rank_acc[g], r);
+}
+
+// The counts are complete: rank, order[rank] = g and the prefill coefficients per position.
+__device__ inline void rank_final_item(const RankArgs& a, int g)
+{
+    if (g < a.n_inst) {
+        const int r = a.rank_acc[g];
+        a.rank_acc[g] = 0;
+        const ClassCoef cc = a.cls[a.inst_class[g]];
+        a.rank[g] = r;
+        a.order[r] = g;
+        // T = E + c0 * (delta + gamma * L); blended: keep * that + lam * p_g * c0
+        const double keep = 1.0 - a.lam;
+        a.posK[r] = a.lam != 0.0 ? make_float2((float)(keep * cc.delta + a.lam * a.emaP[g]), (float)(keep * cc.gamma))
+                                 : make_float2((float)cc.delta, (float)cc.gamma);
+        if (a.out_rank) a.out_rank[g] = r;
+    } else if (g < a.m_pad) {
+        a.order[g] = -1;     // positions past the last instance
+        a.posK[g] = make_float2(0.f, 0.f);
+    }
 }
 
 }  // namespace gr

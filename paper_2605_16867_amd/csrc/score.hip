@@ -49,10 +49,20 @@ __device__ inline bool fetch_len(const ReqSrc& s, int64_t i, int max_len, int& L
 // Requests per length: a histogram private to the workgroup in LDS (two 16-bit
 // counters per word: a workgroup sees at most 1024 * kItems < 65536 requests), then one
 // global atomic per length the workgroup has seen.
+//
+// Workgroups past the first `hist_blocks` do something else that has to happen before the
+// requests are put in order and costs a launch of its own otherwise: the counting step of the
+// capability order (tile b of `rank_bx` x .. tiles, see rank_count_tile; none when rank_bx = 0).
 template <bool kMigrate, int kItems>
-__global__ __launch_bounds__(kGroupBlock) void k_hist(ReqSrc s, int* __restrict__ len_cnt, int bins, int max_len)
+__global__ __launch_bounds__(kGroupBlock) void k_hist(ReqSrc s, int* __restrict__ len_cnt, int bins, int max_len,
+                                                      int hist_blocks, RankArgs ranks, int rank_bx)
 {
     extern __shared__ uint32_t lds[];
+    if ((int)blockIdx.x >= hist_blocks) {
+        const int b = blockIdx.x - hist_blocks;
+        rank_count_tile<kGroupBlock>(ranks, b % rank_bx, b / rank_bx, reinterpret_cast<double*>(lds));
+        return;
+    }
     const int tid = threadIdx.x;
     const int nwords = (bins + 1) / 2;
     for (int w = tid; w < nwords; w += kGroupBlock) lds[w] = 0;
@@ -88,13 +98,19 @@ static_assert(kMaxLen + 1 <= kWave * kScanChunks * kScanWaves * kScanGroups, "ev
 // of passing sums from workgroup to workgroup each workgroup adds up
 // everything before its own lengths itself; the last one also has the totals.
 // The histogram is left as it is (the scatter clears it for the next call).
+// Workgroups past the first kScanGroups finish the capability order (rank_final_item), whose
+// counts the previous launch completed.
 __global__ __launch_bounds__(kScanBlock) void k_scan(const int* __restrict__ len_cnt, int* __restrict__ len_base,
                                                      int* __restrict__ row_len, int* __restrict__ row_off,
                                                      int* __restrict__ tile_off, int* __restrict__ len_row,
                                                      int* __restrict__ len_ceil, int* __restrict__ totals,
-                                                     int* __restrict__ out_n, int bins)
+                                                     int* __restrict__ out_n, int bins, RankArgs ranks)
 {
     __shared__ int w_req[2][kScanWaves], w_tile[2][kScanWaves], w_rows[2][kScanWaves];
+    if (blockIdx.x >= kScanGroups) {
+        rank_final_item(ranks, (blockIdx.x - kScanGroups) * kScanBlock + threadIdx.x);
+        return;
+    }
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const int chunks = (bins + kWave - 1) / kWave;
     const int per = (chunks + kScanWaves * kScanGroups - 1) / (kScanWaves * kScanGroups);    // 1 or 2
@@ -158,7 +174,7 @@ __global__ __launch_bounds__(kScanBlock) void k_scan(const int* __restrict__ len
         at_tile += __builtin_amdgcn_readlane(tile_incl, kWave - 1);
         u += __popcll(present);
     }
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {      // the last workgroup has seen every length
+    if (blockIdx.x == kScanGroups - 1 && threadIdx.x == 0) {      // the last workgroup has seen every length
         row_off[all_rows] = all_req;
         tile_off[all_rows] = all_tile;
         totals[0] = all_req; totals[1] = all_rows; totals[2] = all_tile;
@@ -1367,14 +1383,18 @@ size_t score_lds_bytes(const gr_fleet* f)
     return group > memo ? group : memo;
 }
 
-int score_prepare(gr_fleet* f)
+// Dynamic LDS limits of the kernels that take more than the default.  The attribute belongs to
+// the kernel, not to a handle: it is set to what the largest handle the library accepts needs
+// (hard limits of gr_create), so a later, smaller handle cannot lower it for a live, larger one.
+int score_prepare(gr_fleet*)
 {
-    const size_t hist = (size_t)((f->bins + 1) / 2) * 4, scat = (size_t)f->bins * 4;
+    constexpr size_t hist = (size_t)((kMaxLen + 2) / 2) * 4, scat = (size_t)(kMaxLen + 1) * 4;
+    constexpr size_t memo = sizeof(float) * 2 * kMemoTile + sizeof(int) * kMemoP * kMemoU + (size_t)kMemoP * kMaxEntries * 2;
     const bool ok = set_lds(k_hist<false, 4>, hist) && set_lds(k_hist<true, 4>, hist) &&
                     set_lds(k_hist<false, 16>, hist) && set_lds(k_hist<true, 16>, hist) &&
                     set_lds(k_scatter<false, 4>, scat) && set_lds(k_scatter<true, 4>, scat) &&
                     set_lds(k_scatter<false, 8>, scat) && set_lds(k_scatter<true, 8>, scat) &&
-                    set_lds(k_memo, memo_lds_bytes(f));
+                    set_lds(k_memo, memo);
     return ok ? GR_OK : GR_ERR_HIP;
 }
 
@@ -1429,6 +1449,10 @@ int launch_score_static(gr_fleet* f, const ReqSrc& src, const ScoreOut& out, hip
     // the call can be recorded into a graph
     hipLaunchKernelGGL(k_fill_ones, dim3((unsigned)((src.n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, best, (int)src.n);
     if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
+    if (!f->ranks_current) {       // the capability order of the current status (two small kernels, no allocation)
+        const int rc2 = launch_ranks(f, nullptr, s);
+        if (rc2 != GR_OK) return rc2;
+    }
     return launch_direct(f, src, out, best, s);
 }
 
@@ -1442,8 +1466,22 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     }
     // up to about two million pairs (the default) a thread per pair is cheaper than the five kernels
     // of the grouped pass
-    if (small_batch_ok && !migrate && n <= kDirectMax && n * f->m_pad <= f->small_batch_pairs)
+    if (small_batch_ok && !migrate && n <= kDirectMax && n * f->m_pad <= f->small_batch_pairs) {
+        if (!f->ranks_current) {
+            const int rc = launch_ranks(f, nullptr, s);
+            if (rc != GR_OK) return rc;
+        }
         return launch_direct(f, src, out, f->direct_best, s);
+    }
+    // The capability order of the current status, if nobody has made it yet, rides along with the
+    // first two launches.  While the stream is being captured it always does: a recorded pass may
+    // be replayed after a status build that was recorded elsewhere.
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &capturing) != hipSuccess) return GR_ERR_HIP;
+    const bool with_ranks = !f->ranks_current || capturing != hipStreamCaptureStatusNone;
+    const RankArgs ranks = rank_args(f, nullptr);
+    const int rank_bx = with_ranks ? (f->n_inst + kWave - 1) / kWave : 0;
+    const int rank_blocks = rank_bx * ((f->n_inst + kGroupBlock - 1) / kGroupBlock);
     const int bins = f->bins;
     // requests per workgroup of the grouping kernels.  Every workgroup pays a pass over all length
     // bins and one global atomic per length it has seen: the histogram of a large batch is faster
@@ -1452,20 +1490,25 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     const auto blocks_for = [n](int items) {
         return (unsigned)((n + (int64_t)kGroupBlock * items - 1) / ((int64_t)kGroupBlock * items));
     };
-    const size_t hist_lds = (size_t)((bins + 1) / 2) * 4, scat_lds = (size_t)bins * 4;
+    size_t hist_lds = (size_t)((bins + 1) / 2) * 4;
+    const size_t scat_lds = (size_t)bins * 4;
+    if (hist_lds < kGroupBlock * sizeof(double)) hist_lds = kGroupBlock * sizeof(double);   // (the counting step's competitors)
     const int off = migrate ? kHistMigrate - kHistRoute : 0;
     {
         ProfScope ps(f, kHistRoute + off, s);
-#define GR_LAUNCH_HIST(M, I) hipLaunchKernelGGL((k_hist<M, I>), dim3(blocks_for(I)), dim3(kGroupBlock), hist_lds, s, src, f->len_cnt, bins, f->max_len)
+#define GR_LAUNCH_HIST(M, I) hipLaunchKernelGGL((k_hist<M, I>), dim3(blocks_for(I) + rank_blocks), dim3(kGroupBlock), hist_lds, s, src, \
+                                                f->len_cnt, bins, f->max_len, (int)blocks_for(I), ranks, rank_bx)
         if (migrate) { if (h_items == 16) GR_LAUNCH_HIST(true, 16); else GR_LAUNCH_HIST(true, 4); }
         else { if (h_items == 16) GR_LAUNCH_HIST(false, 16); else GR_LAUNCH_HIST(false, 4); }
 #undef GR_LAUNCH_HIST
     }
     {
         ProfScope ps(f, kScanRoute + off, s);
-        hipLaunchKernelGGL(k_scan, dim3(kScanGroups), dim3(kScanBlock), 0, s, f->len_cnt, f->len_base, f->row_len,
-                           f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, out.n_selected, bins);
+        const int final_blocks = with_ranks ? (f->m_pad + kScanBlock - 1) / kScanBlock : 0;
+        hipLaunchKernelGGL(k_scan, dim3(kScanGroups + final_blocks), dim3(kScanBlock), 0, s, f->len_cnt, f->len_base, f->row_len,
+                           f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, out.n_selected, bins, ranks);
     }
+    if (with_ranks) f->ranks_current = true;
     {
         ProfScope ps(f, kScatterRoute + off, s);
 #define GR_LAUNCH_SCATTER(M, I) hipLaunchKernelGGL((k_scatter<M, I>), dim3(blocks_for(I)), dim3(kGroupBlock), scat_lds, s, src, \

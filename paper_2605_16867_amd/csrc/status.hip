@@ -770,52 +770,17 @@ __global__ __launch_bounds__(kBlock, (kEPL <= 8 ? 4 : 1)) void k_build_lean(Buil
     }
 }
 
-// Capability order of Alg. 1's argmax d_g: rank 0 = largest d_g, equal d_g by
-// index.  rank_g = #{h : d_h > d_g} + #{h < g : d_h = d_g}, counted over tiles of
-// 64 instances x 256 competitors and added up with atomics.
-__global__ __launch_bounds__(kBlock) void k_rank_count(const double* __restrict__ d, int n_inst,
-                                                       int* __restrict__ rank_acc)
+// Capability order of Alg. 1's argmax d_g as two kernels of their own (see common.h for the
+// steps; a scoring pass normally runs them as extra workgroups of its first two kernels).
+__global__ __launch_bounds__(kBlock) void k_rank_count(RankArgs a)
 {
     __shared__ double comp[kBlock];
-    const int tid = threadIdx.x;
-    const int g = blockIdx.x * kWave + (tid & (kWave - 1));
-    const int h0 = blockIdx.y * kBlock;
-    comp[tid] = h0 + tid < n_inst ? d[h0 + tid] : 0.0;
-    __syncthreads();
-    if (g >= n_inst) return;
-    const double dg = d[g];
-    const int part = tid / kWave;                 // which 64 of the 256 competitors
-    const int lim = min(kWave, n_inst - h0 - part * kWave);
-    int r = 0;
-    for (int j = 0; j < lim; ++j) {
-        const double dh = comp[part * kWave + j];
-        r += (dh > dg) || (dh == dg && h0 + part * kWave + j < g);
-    }
-    if (r) atomicAdd(&rank_acc[g], r);
+    rank_count_tile<kBlock>(a, blockIdx.x, blockIdx.y, comp);
 }
 
-__global__ __launch_bounds__(kBlock) void k_rank_final(const int* __restrict__ rank_acc, int n_inst, int m_pad,
-                                                       const ClassCoef* __restrict__ cls,
-                                                       const int* __restrict__ inst_class,
-                                                       double lam, const double* __restrict__ emaP,
-                                                       int* __restrict__ rank, int* __restrict__ order,
-                                                       float2* __restrict__ posK, int* __restrict__ out_rank)
+__global__ __launch_bounds__(kBlock) void k_rank_final(RankArgs a)
 {
-    const int g = blockIdx.x * kBlock + threadIdx.x;
-    if (g < n_inst) {
-        const int r = rank_acc[g];
-        const ClassCoef cc = cls[inst_class[g]];
-        rank[g] = r;
-        order[r] = g;
-        // T = E + c0 * (delta + gamma * L); blended: keep * that + lam * p_g * c0
-        const double keep = 1.0 - lam;
-        posK[r] = lam != 0.0 ? make_float2((float)(keep * cc.delta + lam * emaP[g]), (float)(keep * cc.gamma))
-                             : make_float2((float)cc.delta, (float)cc.gamma);
-        if (out_rank) out_rank[g] = r;
-    } else if (g < m_pad) {
-        order[g] = -1;     // positions past the last instance
-        posK[g] = make_float2(0.f, 0.f);
-    }
+    rank_final_item(a, blockIdx.x * kBlock + threadIdx.x);
 }
 
 // One step of the exponential moving average of Alg. 1, q <- w * sample + (1 - w) * q, for
@@ -900,6 +865,49 @@ int launch_ema(gr_fleet* f, double w, const float* s_q, const float* s_p, const 
     return GR_OK;
 }
 
+// Dynamic LDS limits of the build kernels, set to what each needs at most (see score_prepare).
+int status_prepare()
+{
+    bool ok = true;
+    const auto set = [&](auto kernel, size_t bytes) {
+        ok = ok && hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)bytes) == hipSuccess;
+    };
+    constexpr size_t word = kBuildWaves * kWave * sizeof(int);     // per sort word per lane
+    set(k_build_lean<1>, word * 1); set(k_build_lean<2>, word * 2); set(k_build_lean<4>, word * 4);
+    set(k_build_lean<8>, word * 8); set(k_build_lean<16>, word * 16); set(k_build_lean<32>, word * 32);
+    set(k_build_capped<1>, 3 * word * 1); set(k_build_capped<2>, 3 * word * 2); set(k_build_capped<4>, 3 * word * 4);
+    set(k_build_capped<8>, 3 * word * 8); set(k_build_capped<16>, 3 * word * 16); set(k_build_capped<32>, 3 * word * 32);
+    return ok ? GR_OK : GR_ERR_HIP;
+}
+
+RankArgs rank_args(const gr_fleet* f, int* out_rank)
+{
+    RankArgs r{};
+    r.d = f->hD; r.rank_acc = f->rank_acc; r.cls = f->cls; r.inst_class = f->inst_class;
+    r.emaP = f->emaP; r.lam = f->lam_built;
+    r.rank = f->rank; r.order = f->order; r.posK = f->posK; r.out_rank = out_rank;
+    r.n_inst = f->n_inst; r.m_pad = f->m_pad;
+    return r;
+}
+
+int launch_ranks(gr_fleet* f, int* out_rank, hipStream_t s)
+{
+    const RankArgs r = rank_args(f, out_rank);
+    const int M = f->n_inst;
+    {
+        ProfScope ps(f, kRankCount, s);
+        hipLaunchKernelGGL(k_rank_count, dim3((M + kWave - 1) / kWave, (M + kBlock - 1) / kBlock), dim3(kBlock), 0, s, r);
+    }
+    {
+        ProfScope ps(f, kRankFinal, s);
+        hipLaunchKernelGGL(k_rank_final, dim3((f->m_pad + kBlock - 1) / kBlock), dim3(kBlock), 0, s, r);
+    }
+    if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
+    f->ranks_current = true;
+    return GR_OK;
+}
+
 int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
 {
     BuildArgs b{};
@@ -931,20 +939,15 @@ int launch_status(gr_fleet* f, const StatusIn& in, hipStream_t s)
             default: launch_build<32>(b, M, s); break;
         }
     }
-    {
-        ProfScope ps(f, kRankCount, s);
-        hipLaunchKernelGGL(k_rank_count, dim3((M + kWave - 1) / kWave, (M + kBlock - 1) / kBlock),
-                           dim3(kBlock), 0, s, f->hD, M, f->rank_acc);
-    }
-    {
-        ProfScope ps(f, kRankFinal, s);
-        hipLaunchKernelGGL(k_rank_final, dim3((f->m_pad + kBlock - 1) / kBlock), dim3(kBlock), 0, s,
-                           f->rank_acc, M, f->m_pad, f->cls, f->inst_class, f->lam, f->emaP, f->rank, f->order,
-                           f->posK, in.out_rank);
+    // the capability order: now if the caller wants to see it, else with the next scoring pass
+    f->ranks_current = false;
+    f->lam_built = f->lam;
+    if (in.out_rank) {
+        const int rc = launch_ranks(f, in.out_rank, s);
+        if (rc != GR_OK) return rc;
     }
     if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
     f->has_status = true;
-    f->lam_built = f->lam;
     f->tables_current = true;
     if (!in.use_pending) f->last_in = in;     // what a later feedback routing rebuilds from
     return GR_OK;
