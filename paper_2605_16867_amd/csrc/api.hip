@@ -10,8 +10,8 @@ namespace {
 
 const char* const kKernelNames[kNumKernels] = {
     "k_build", "k_rank_count", "k_rank_final",
-    "k_hist<route>", "k_scan<route>", "k_scatter<route>", "k_memo<route>", "k_tile<route>",
-    "k_hist<migrate>", "k_scan<migrate>", "k_scatter<migrate>", "k_memo<migrate>", "k_tile<migrate>",
+    "k_hist<route>", "k_scan<route>", "k_group<route>", "k_tile<route>",
+    "k_hist<migrate>", "k_scan<migrate>", "k_group<migrate>", "k_tile<migrate>",
     "k_hits<route>", "k_direct", "k_direct_finish"};
 
 template <typename T>

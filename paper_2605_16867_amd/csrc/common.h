@@ -75,8 +75,8 @@ struct ScoreOut {
 };
 
 enum KernelId {
-    kBuild = 0, kRankCount, kRankFinal, kHistRoute, kScanRoute, kScatterRoute, kMemoRoute, kTileRoute,
-    kHistMigrate, kScanMigrate, kScatterMigrate, kMemoMigrate, kTileMigrate, kHitsRoute, kDirect, kDirectFinish,
+    kBuild = 0, kRankCount, kRankFinal, kHistRoute, kScanRoute, kGroupRoute, kTileRoute,
+    kHistMigrate, kScanMigrate, kGroupMigrate, kTileMigrate, kHitsRoute, kDirect, kDirectFinish,
     kNumKernels
 };
 

@@ -182,22 +182,37 @@ __global__ __launch_bounds__(kScanBlock) void k_scan(const int* __restrict__ len
     }
 }
 
+struct ScatterArgs {
+    ReqSrc s;
+    int *len_cnt, *len_base;
+    const int* rank;
+    ReqRec* recs;
+    int* out_inst;
+    float* out_slack;
+    int bins, max_len, n_inst;
+};
+
 // Requests into grouped order.  Per workgroup: count per length in LDS, reserve
 // that many slots of each length with one global atomic, hand the slots out.
+// Workgroup `block` of `blocks`.
 template <bool kMigrate, int kItems>
-__global__ __launch_bounds__(kGroupBlock) void k_scatter(ReqSrc s, int* __restrict__ len_cnt, int* __restrict__ len_base,
-                                                    const int* __restrict__ rank, ReqRec* __restrict__ recs,
-                                                    int* __restrict__ out_inst, float* __restrict__ out_slack,
-                                                    int bins, int max_len, int n_inst)
+__device__ __forceinline__ void scatter_block(const ScatterArgs& a, int block, int blocks, uint32_t* lds)
 {
-    extern __shared__ uint32_t lds[];
+    const ReqSrc& s = a.s;
+    int* const len_cnt = a.len_cnt;
+    int* const len_base = a.len_base;
+    const int* const rank = a.rank;
+    ReqRec* const recs = a.recs;
+    int* const out_inst = a.out_inst;
+    float* const out_slack = a.out_slack;
+    const int bins = a.bins, max_len = a.max_len, n_inst = a.n_inst;
     int* slot = reinterpret_cast<int*>(lds);
     const int tid = threadIdx.x;
     for (int L = tid; L < bins; L += kGroupBlock) slot[L] = 0;
     // the histogram has been turned into slot bases: clear it for the next call
-    for (int L = blockIdx.x * kGroupBlock + tid; L < bins; L += gridDim.x * kGroupBlock) len_cnt[L] = 0;
+    for (int L = block * kGroupBlock + tid; L < bins; L += blocks * kGroupBlock) len_cnt[L] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * (kGroupBlock * kItems);
+    const int64_t base = (int64_t)block * (kGroupBlock * kItems);
     int Ls[kItems];
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
@@ -275,12 +290,12 @@ constexpr int kMemoTile = kMemoU * (kMemoP + 1);       // floats
 static_assert(kMemoU == 4 * kWave, "a lane owns four consecutive counters");
 static_assert(kMemoP == 16, "a length's values of one workgroup sit in one row of 16 lanes");
 
-__global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
+// Workgroup (bx, by) of gx x gy.
+__device__ __forceinline__ void memo_block(const MemoArgs& a, int bx, int by, int gx, int gy, uint32_t* lds)
 {
-    extern __shared__ uint32_t lds[];
     float* tiles = reinterpret_cast<float*>(lds);
     const int U = a.totals[1];
-    const int p0 = blockIdx.x * kMemoP;
+    const int p0 = bx * kMemoP;
     const int tid = threadIdx.x, lane = lane_id(), pi = tid / kWave;
     int* cnt = reinterpret_cast<int*>(tiles + 2 * kMemoTile) + pi * kMemoU;
     uint16_t* sRow = reinterpret_cast<uint16_t*>(tiles + 2 * kMemoTile + kMemoP * kMemoU) + (size_t)pi * a.cap;
@@ -288,8 +303,8 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
     const int p = p0 + pi;
     const int g = p < a.n_inst ? a.order[p] : -1;
     // this workgroup's run of rows
-    const int per = ((U + (int)gridDim.y - 1) / (int)gridDim.y + kMemoU - 1) / kMemoU * kMemoU;
-    const int ub = blockIdx.y * per, ue = min(ub + per, U);
+    const int per = ((U + gy - 1) / gy + kMemoU - 1) / kMemoU * kMemoU;
+    const int ub = by * per, ue = min(ub + per, U);
     int N = 0;
     float2 head = make_float2(0.f, 0.f);
     float gam = 0.f;
@@ -310,14 +325,14 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     // the least delta and gamma of this workgroup's positions, for the scoring kernel's bounds
-    if (blockIdx.y == 0 && tid < kMemoP) {
+    if (by == 0 && tid < kMemoP) {
         float2 k = a.posK[p0 + tid];
 #pragma unroll
         for (int d = 1; d < kMemoP; d <<= 1) {
             k.x = fminf(k.x, __shfl_xor(k.x, d, kMemoP));
             k.y = fminf(k.y, __shfl_xor(k.y, d, kMemoP));
         }
-        if (tid == 0) a.grp_k[blockIdx.x] = k;
+        if (tid == 0) a.grp_k[bx] = k;
     }
 
     // entries that belong to rows before the run (the rows are ascending with the entries: the
@@ -344,7 +359,7 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
         float* tile = tiles + buf * kMemoTile;
         // the row of every tile, for the scoring kernel: the pass's rows are shared out over the
         // workgroups of this run of rows and their waves (usually one row per workgroup and pass)
-        for (int r = blockIdx.x + gridDim.x * pi; r < kMemoU; r += gridDim.x * kMemoP) {
+        for (int r = bx + gx * pi; r < kMemoU; r += gx * kMemoP) {
             const int u = u0 + r;
             if (u >= ue) break;
             const int t0 = a.tile_off[u], t1 = a.tile_off[u + 1];
@@ -423,9 +438,26 @@ __global__ __launch_bounds__(kMemoBlock) void k_memo(MemoArgs a)
                          "v_min_f32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
                          "s_nop 1"
                          : "+v"(m));
-            if (u < U && col == kMemoP - 1) a.grp_min[(size_t)blockIdx.x * a.row_cap + u] = m;
+            if (u < U && col == kMemoP - 1) a.grp_min[(size_t)bx * a.row_cap + u] = m;
         }
     }
+}
+
+static_assert(kMemoBlock == kGroupBlock, "the two halves of k_group share a workgroup shape");
+
+// The two kernels between the prefix sums and the tiles do not depend on each other (one puts
+// the requests in grouped order, the other tabulates E per distinct length and position), so
+// they share a launch and run side by side: workgroups 0 .. memo_blocks - 1 tabulate, the
+// others scatter.
+template <bool kMigrate, int kItems>
+__global__ __launch_bounds__(kGroupBlock) void k_group(ScatterArgs sa, MemoArgs ma, int memo_gx, int memo_gy)
+{
+    extern __shared__ uint32_t lds[];
+    const int memo_blocks = memo_gx * memo_gy;
+    if ((int)blockIdx.x < memo_blocks)
+        memo_block(ma, blockIdx.x % memo_gx, blockIdx.x / memo_gx, memo_gx, memo_gy, lds);
+    else
+        scatter_block<kMigrate, kItems>(sa, blockIdx.x - memo_blocks, gridDim.x - memo_blocks, lds);
 }
 
 // ------------------------------------------------------------------ Alg. 1 over tiles
@@ -1390,11 +1422,11 @@ int score_prepare(gr_fleet*)
 {
     constexpr size_t hist = (size_t)((kMaxLen + 2) / 2) * 4, scat = (size_t)(kMaxLen + 1) * 4;
     constexpr size_t memo = sizeof(float) * 2 * kMemoTile + sizeof(int) * kMemoP * kMemoU + (size_t)kMemoP * kMaxEntries * 2;
+    constexpr size_t group = scat > memo ? scat : memo;
     const bool ok = set_lds(k_hist<false, 4>, hist) && set_lds(k_hist<true, 4>, hist) &&
                     set_lds(k_hist<false, 16>, hist) && set_lds(k_hist<true, 16>, hist) &&
-                    set_lds(k_scatter<false, 4>, scat) && set_lds(k_scatter<true, 4>, scat) &&
-                    set_lds(k_scatter<false, 8>, scat) && set_lds(k_scatter<true, 8>, scat) &&
-                    set_lds(k_memo, memo);
+                    set_lds(k_group<false, 4>, group) && set_lds(k_group<true, 4>, group) &&
+                    set_lds(k_group<false, 8>, group) && set_lds(k_group<true, 8>, group);
     return ok ? GR_OK : GR_ERR_HIP;
 }
 
@@ -1509,28 +1541,27 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
                            f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, out.n_selected, bins, ranks);
     }
     if (with_ranks) f->ranks_current = true;
-    {
-        ProfScope ps(f, kScatterRoute + off, s);
-#define GR_LAUNCH_SCATTER(M, I) hipLaunchKernelGGL((k_scatter<M, I>), dim3(blocks_for(I)), dim3(kGroupBlock), scat_lds, s, src, \
-                                                   f->len_cnt, f->len_base, f->rank, f->recs, out.inst, out.slack, bins, f->max_len, f->n_inst)
-        if (migrate) { if (s_items == 8) GR_LAUNCH_SCATTER(true, 8); else GR_LAUNCH_SCATTER(true, 4); }
-        else { if (s_items == 8) GR_LAUNCH_SCATTER(false, 8); else GR_LAUNCH_SCATTER(false, 4); }
-#undef GR_LAUNCH_SCATTER
-    }
     const int64_t max_rows = n < bins ? n : bins;
     {
+        ScatterArgs sc{};
+        sc.s = src; sc.len_cnt = f->len_cnt; sc.len_base = f->len_base; sc.rank = f->rank; sc.recs = f->recs;
+        sc.out_inst = out.inst; sc.out_slack = out.slack; sc.bins = bins; sc.max_len = f->max_len; sc.n_inst = f->n_inst;
         MemoArgs m{};
         m.totals = f->totals; m.row_len = f->row_len; m.len_ceil = f->len_ceil; m.order = f->order; m.hN = f->hN;
         m.cls = f->cls; m.inst_class = f->inst_class;
         m.tabR = f->tabR; m.tabGH = f->tabGH; m.headGH = f->headGH; m.memo = f->memo; m.grp_min = f->grp_min; m.grp_k = f->grp_k; m.posK = f->posK; m.tile_off = f->tile_off; m.tile_row = f->tile_row; m.row_cap = (int)f->row_cap;
         m.n_inst = f->n_inst; m.m_pad = f->m_pad; m.cap = f->cap; m.keep = (float)(1.0 - f->lam_built);
-        // every workgroup walks all lengths; with few instances the lengths are dealt out to several
+        // every memo workgroup walks all lengths; with few instances the lengths are dealt out to several
         const int gx = f->m_pad / kMemoP;
         const int64_t chunks = (max_rows + kMemoU - 1) / kMemoU;
         int gy = gx >= 512 ? 1 : 512 / gx;
         if (gy > chunks) gy = (int)chunks;
-        ProfScope ps(f, kMemoRoute + off, s);
-        hipLaunchKernelGGL(k_memo, dim3(gx, gy), dim3(kMemoBlock), memo_lds_bytes(f), s, m);
+        const size_t memo_lds = memo_lds_bytes(f), lds = scat_lds > memo_lds ? scat_lds : memo_lds;
+        ProfScope ps(f, kGroupRoute + off, s);
+#define GR_LAUNCH_GROUP(M, I) hipLaunchKernelGGL((k_group<M, I>), dim3(gx * gy + blocks_for(I)), dim3(kGroupBlock), lds, s, sc, m, gx, gy)
+        if (migrate) { if (s_items == 8) GR_LAUNCH_GROUP(true, 8); else GR_LAUNCH_GROUP(true, 4); }
+        else { if (s_items == 8) GR_LAUNCH_GROUP(false, 8); else GR_LAUNCH_GROUP(false, 4); }
+#undef GR_LAUNCH_GROUP
     }
     {
         TileArgs t{};
