@@ -42,10 +42,38 @@ OPS_PER_PAIR = 3.0
 # the risk scan also reads the budget (4 B) and writes the flag (1 B).
 BUILD_BYTES_PER_ENTRY = 26.0
 SCAN_EXTRA_BYTES_PER_ENTRY = 5.0
-# HBM bytes per launch of the dominant kernel (k_tile, migration launch of the "heavy" fleet) from
-# the rocprofv3 counter passes summarised under profiles/, scaled by the plain-copy calibration;
-# None whenever that kernel has changed since the counters were taken.
-TILE_MIGRATE_HEAVY_TRAFFIC_BYTES = int((249.2 + 132.4) * 2**20)   # fetch + write MiB per launch
+# HBM bytes per launch of the dominant kernel come from the rocprofv3 counter passes summarised
+# under profiles/ (not from this run): the summary of a workload carries a line
+#   traffic-record: kernel=<name> fetch_bytes=<n> write_bytes=<n> sources_sha256=<hash>
+# with the hash of the kernel sources the counters were taken with.  The figure is reported only
+# while those sources are unchanged; otherwise null.
+KERNEL_SOURCES = ("paper_2605_16867_amd/csrc/score.hip", "paper_2605_16867_amd/csrc/status.hip",
+                  "paper_2605_16867_amd/csrc/common.h")
+
+
+def sources_sha256() -> str:
+    import hashlib
+    h = hashlib.sha256()
+    for rel in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, rel), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def recorded_traffic(workload: str, kernel: str):
+    """(fetch + write bytes per launch, where it is from) or (None, why not)."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_step_all_kernels.md")
+    if not os.path.exists(path):
+        return None, "no counter summary for this workload under profiles/"
+    for line in open(path):
+        if line.startswith("traffic-record:"):
+            kv = dict(item.split("=", 1) for item in line.split()[1:])
+            if kv.get("kernel") != kernel:
+                continue
+            if kv.get("sources_sha256") != sources_sha256():
+                return None, "kernel sources changed since the counters in profiles/ were taken"
+            return int(kv["fetch_bytes"]) + int(kv["write_bytes"]), os.path.relpath(path, ROOT)
+    return None, "no traffic record for this kernel under profiles/"
 
 
 def parse():
@@ -112,8 +140,12 @@ def cpu_baseline(fl, pairs_route, pairs_migrate, entries, n_flagged, target_s):
     if n_mig:
         est += t_mig * len(flag) / n_mig
     total_pairs = pairs_route + len(flag) * (M - 1) + 2 * entries
+    calls = {"gr_build_status": t_sim,
+             "gr_score_route": (t_route * R / n_route) if n_route else 0.0,
+             "gr_risk_scan": t_sim2 + ((t_mig * len(flag) / n_mig) if n_mig else 0.0)}
     return {
         "value": total_pairs / est, "unit": "pairs/s", "cores": oracle.threads(), "kind": "oracle",
+        "seconds_per_call": calls,
         "sample": (f"both step-by-step simulations of all {M} instances ({t_sim + t_sim2:.2f} s), "
                    f"exhaustive scan of {n_route} of {R} incoming requests ({t_route:.2f} s) and of "
                    f"{n_mig} of {len(flag)} flagged requests ({t_mig:.2f} s), scan times scaled to the "
@@ -196,7 +228,8 @@ def main():
     for _ in range(a.steps):
         step()
     torch.cuda.synchronize()
-    prof_all = h.gr_profile_read()
+    launches_all = h.gr_profile_read_launches(prof_slots * a.steps)
+    prof_all = {n: (sum(v), len(v)) for n, v in launches_all.items()}
     heaviest = max((n for n in prof_all if n.startswith(("k_tile", "k_build")) and prof_all[n][1]),
                    key=lambda n: prof_all[n][0])
     # timed region: HIP events around the launches of that kernel only (an event pair costs a few
@@ -209,12 +242,13 @@ def main():
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    prof = h.gr_profile_read()
+    launches = h.gr_profile_read_launches(prof_slots * a.steps)
     h.gr_profile_select(None)
     h.gr_profile_enable(0)
-    for name, v in prof_all.items():
-        if not prof.get(name, (0.0, 0))[1]:
-            prof[name] = v
+    for name, v in launches_all.items():
+        if not launches.get(name):
+            launches[name] = v
+    prof = {n: (sum(v), len(v)) for n, v in launches.items()}
 
     # route-batch latency: gr_score_route alone on the warm handle, host clock around call + sync
     route_ms = []
@@ -247,7 +281,9 @@ def main():
         if not cnt:
             continue
         avg_ms = ms / cnt
-        k = {"avg_ms": avg_ms, "launches_per_step": cnt / a.steps}
+        each = sorted(launches[name])
+        k = {"avg_ms": avg_ms, "median_ms": each[len(each) // 2], "p99_ms": each[min(len(each) - 1, int(0.99 * len(each)))],
+             "launches_per_step": cnt / a.steps}
         if name.startswith("k_tile"):
             pairs = (pairs_route if "route" in name else pairs_mig) / (cnt / a.steps)     # per launch
             k.update(bound="alu", pairs=pairs, pairs_per_s=pairs / (avg_ms * 1e-3),
@@ -263,9 +299,10 @@ def main():
     dominant = max((n for n in kernels if "bound" in kernels[n]),
                    key=lambda n: kernels[n]["avg_ms"] * kernels[n]["launches_per_step"])
     dk = kernels[dominant]
-    traffic = TILE_MIGRATE_HEAVY_TRAFFIC_BYTES if (dominant == "k_tile<migrate>" and a.config == "heavy") else None
+    traffic, traffic_from = (recorded_traffic(a.config, dominant) if not variant
+                             else (None, "variant run: no counters taken"))
     roofline = {"kernel": dominant, "bound": dk["bound"], "achieved": dk["achieved"], "peak": dk["peak"],
-                "unit": dk["unit"], "frac": dk["frac"], "traffic": traffic,
+                "unit": dk["unit"], "frac": dk["frac"], "traffic": traffic, "traffic_from": traffic_from,
                 "avg_launch_ms": dk["avg_ms"]}
 
     out = {
@@ -291,7 +328,7 @@ def main():
     if "frac" in kernels["k_build"]:
         out["hbm_pct_of_peak"]["k_build (algorithmic bytes)"] = 100.0 * kernels["k_build"]["frac"]
     if traffic is not None:
-        out["hbm_pct_of_peak"][dominant + " (counter bytes)"] = (
+        out["hbm_pct_of_peak"][dominant + " (counter bytes from " + traffic_from + ")"] = (
             100.0 * traffic / (dk["avg_ms"] * 1e-3) / (HBM_PEAK_GBS * 1e9))
     if a.cpu_seconds > 0:
         out["cpu_baseline"] = cpu_baseline(fl, pairs_route, pairs_mig, entries, n_flagged, a.cpu_seconds)

@@ -340,10 +340,14 @@ int gr_device_status(gr_fleet* f, int32_t* out_bits);
  * gr_profile_select restricts the timing to the kernel ids whose bit is set in
  * kernel_mask (all of them after gr_create): an event pair costs a few
  * microseconds of stream time, which adds up over a dozen short launches.
+ * gr_profile_read_launches is gr_profile_read launch by launch, in launch order:
+ * kernel id and elapsed milliseconds of up to max_launches recorded launches
+ * into HOST arrays, their number into *n_launches (for medians and percentiles).
  */
 int gr_profile_enable(gr_fleet* f, int32_t max_launches);
 int gr_profile_select(gr_fleet* f, uint64_t kernel_mask);
 int gr_profile_read(gr_fleet* f, int32_t n_kernels, double* total_ms, int64_t* launches);
+int gr_profile_read_launches(gr_fleet* f, int32_t max_launches, int32_t* kernel_id, float* ms, int32_t* n_launches);
 int32_t gr_profile_kernel_count(void);
 const char* gr_profile_kernel_name(int32_t id);
 

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libgoodroute.so")
 EXPORTS = ("gr_create", "gr_destroy", "gr_build_status", "gr_score_route", "gr_score_route_noalloc", "gr_score_route_cached", "gr_route_feedback",
            "gr_risk_scan", "gr_observe", "gr_set_blend", "gr_set_batch_cap", "gr_set_small_batch_pairs",
            "gr_device_status", "gr_strerror", "gr_profile_enable", "gr_profile_select", "gr_profile_read",
-           "gr_profile_kernel_count", "gr_profile_kernel_name")
+           "gr_profile_read_launches", "gr_profile_kernel_count", "gr_profile_kernel_name")
 
 _lib = None
 
@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
         l.gr_profile_select.argtypes = [p, C.c_uint64]
         l.gr_profile_read.restype = C.c_int
         l.gr_profile_read.argtypes = [p, i32, p, p]
+        l.gr_profile_read_launches.restype = C.c_int
+        l.gr_profile_read_launches.argtypes = [p, i32, p, p, p]
         l.gr_profile_kernel_count.restype = i32
         l.gr_profile_kernel_count.argtypes = []
         l.gr_profile_kernel_name.restype = C.c_char_p
@@ -249,6 +251,17 @@ class Fleet:
         cnt = (C.c_int64 * n)()
         _check(lib().gr_profile_read(self._h, n, ms, cnt), "gr_profile_read")
         return {lib().gr_profile_kernel_name(k).decode(): (float(ms[k]), int(cnt[k])) for k in range(n)}
+
+    def gr_profile_read_launches(self, max_launches: int) -> dict:
+        """{kernel name: [milliseconds of each recorded launch, in launch order]} since the last read."""
+        ids = (C.c_int32 * max(max_launches, 1))()
+        ms = (C.c_float * max(max_launches, 1))()
+        n = C.c_int32(0)
+        _check(lib().gr_profile_read_launches(self._h, int(max_launches), ids, ms, C.byref(n)), "gr_profile_read_launches")
+        out = {}
+        for i in range(int(n.value)):
+            out.setdefault(lib().gr_profile_kernel_name(ids[i]).decode(), []).append(float(ms[i]))
+        return out
 
     def gr_device_status(self) -> int:
         bits = C.c_int32(0)

@@ -378,6 +378,21 @@ int gr_profile_read(gr_fleet* f, int32_t n_kernels, double* total_ms, int64_t* l
     return GR_OK;
 }
 
+int gr_profile_read_launches(gr_fleet* f, int32_t max_launches, int32_t* kernel_id, float* ms, int32_t* n_launches)
+{
+    if (!f || max_launches < 0 || !n_launches || (max_launches > 0 && (!kernel_id || !ms))) return GR_ERR_INVALID_ARG;
+    if (hipDeviceSynchronize() != hipSuccess) return GR_ERR_HIP;
+    Profiler& p = f->prof;
+    const size_t n = p.ids.size() < (size_t)max_launches ? p.ids.size() : (size_t)max_launches;
+    for (size_t i = 0; i < n; ++i) {
+        if (hipEventElapsedTime(&ms[i], p.events[2 * i], p.events[2 * i + 1]) != hipSuccess) return GR_ERR_HIP;
+        kernel_id[i] = p.ids[i];
+    }
+    *n_launches = (int32_t)n;
+    p.ids.clear();
+    return GR_OK;
+}
+
 int32_t gr_profile_kernel_count(void) { return kNumKernels; }
 
 const char* gr_profile_kernel_name(int32_t id)
