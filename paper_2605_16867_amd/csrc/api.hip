@@ -86,7 +86,7 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
         dev_alloc(&f->emaQ, n_inst) && dev_alloc(&f->emaP, n_inst) && dev_alloc(&f->emaD, n_inst) &&
         dev_alloc(&f->rank_acc, n_inst) && dev_alloc(&f->rank, n_inst) && dev_alloc(&f->order, f->m_pad) && dev_alloc(&f->posK, f->m_pad) &&
         dev_alloc(&f->act_inst, f->max_active) && dev_alloc(&f->counters, 1) &&
-        dev_alloc(&f->pend_cnt, n_inst) && dev_alloc(&f->pend_touched, n_inst) && dev_alloc(&f->pend_prompt, tab) && dev_alloc(&f->pend_len, tab) &&
+        dev_alloc(&f->pend_cnt, n_inst) && dev_alloc(&f->commit_mark, n_inst) && dev_alloc(&f->pend_touched, n_inst) && dev_alloc(&f->pend_prompt, tab) && dev_alloc(&f->pend_len, tab) &&
         dev_alloc(&f->scratch_finish, f->max_active) && dev_alloc(&f->batch_cap, n_inst) &&
         dev_alloc(&f->len_cnt, f->bins) && dev_alloc(&f->len_base, f->bins) &&
         dev_alloc(&f->row_len, f->row_cap) && dev_alloc(&f->row_off, f->row_cap + 1) &&
@@ -107,9 +107,10 @@ int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
     const hipError_t e5 = hipMemset(f->totals, 0, sizeof(int) * 4);
     const hipError_t e6 = hipMemset(f->pend_cnt, 0, sizeof(int) * n_inst);
     const hipError_t e8 = hipMemset(f->pend_touched, 0, sizeof(int) * n_inst);
+    const hipError_t e9 = hipMemset(f->commit_mark, 0, sizeof(int) * n_inst);
     const hipError_t e7 = hipMemset(f->direct_best, 0xFF, sizeof(unsigned long long) * 2 * kDirectMax);
     free(host);
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess || e6 != hipSuccess || e7 != hipSuccess || e8 != hipSuccess ||
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess || e5 != hipSuccess || e6 != hipSuccess || e7 != hipSuccess || e8 != hipSuccess || e9 != hipSuccess ||
         hipDeviceSynchronize() != hipSuccess) {
         gr_destroy(f);
         return GR_ERR_HIP;
@@ -129,7 +130,7 @@ int gr_destroy(gr_fleet* f)
     if (!f) return GR_OK;
     (void)hipDeviceSynchronize();
     void* ptrs[] = {f->cls, f->inst_class, f->tabR, f->tabGH, f->headGH, f->hN, f->hD, f->emaQ, f->emaP, f->emaD, f->rank_acc,
-                    f->rank, f->order, f->posK, f->act_inst, f->pend_cnt, f->pend_touched, f->pend_prompt, f->pend_len,
+                    f->rank, f->order, f->posK, f->act_inst, f->pend_cnt, f->commit_mark, f->pend_touched, f->pend_prompt, f->pend_len,
                     f->scratch_finish, f->batch_cap, f->counters, f->len_cnt, f->len_base, f->row_len,
                     f->row_off, f->tile_off, f->len_row, f->len_ceil, f->totals, f->recs, f->memo, f->tile_row, f->grp_min, f->grp_k, f->direct_best};
     int rc = GR_OK;

@@ -138,6 +138,7 @@ struct gr_fleet {
     // feedback routing: the caller's last status inputs, and the requests routed since, per instance
     gr::StatusIn last_in{};
     int* pend_cnt = nullptr;      // [M]
+    int* commit_mark = nullptr;   // [M] 1: chosen by a request of the chunk being committed (all zero between commits)
     int* pend_prompt = nullptr;   // [M][cap]
     int* pend_len = nullptr;      // [M][cap]
     float* scratch_finish = nullptr;  // [max_active] finish times of rebuilds nobody asked to see

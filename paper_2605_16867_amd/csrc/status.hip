@@ -797,19 +797,21 @@ __global__ __launch_bounds__(kBlock) void k_ema(int n_inst, double w, const floa
     if (s_d) d[g] = first_d ? (double)s_d[g] : w * (double)s_d[g] + (1.0 - w) * d[g];
 }
 
-// Requests that were routed join the queue of their instance (feedback routing): one slot of
-// the instance's list per request.  Many requests of a chunk go to the same instance and
-// atomics on one address are served one after the other, so the lanes of a wave that chose
-// the same instance reserve their slots with one atomic.
-__global__ __launch_bounds__(kBlock) void k_commit(int64_t n, const int* __restrict__ inst,
-                                                   const int* __restrict__ ctx0, const int* __restrict__ pred_len,
-                                                   int* __restrict__ pend_cnt, int* __restrict__ pend_prompt,
-                                                   int* __restrict__ pend_len, int* __restrict__ pend_touched,
-                                                   int cap, int n_inst, int* __restrict__ counters)
+// Requests that were routed join the queue of their instance (feedback routing), in the order of
+// the batch: the slot of a request is the number of requests already queued there plus the number
+// of earlier requests of the chunk that were sent to the same instance.  That order matters under
+// batch caps (admission is first come, first served), so it must not depend on how the hardware
+// schedules waves.  A chunk that fits one wave is placed by that wave (lanes are in request
+// order).  A larger chunk takes two kernels: the first marks the instances that were chosen at
+// all, the second gives every marked instance a wave that walks the chunk in order.
+__global__ __launch_bounds__(kWave) void k_commit_wave(int n, const int* __restrict__ inst,
+                                                       const int* __restrict__ ctx0, const int* __restrict__ pred_len,
+                                                       int* __restrict__ pend_cnt, int* __restrict__ pend_prompt,
+                                                       int* __restrict__ pend_len, int* __restrict__ pend_touched,
+                                                       int cap, int n_inst, int* __restrict__ counters)
 {
-    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
     const int lane = lane_id();
-    int g = i < n ? inst[i] : -1;
+    int g = lane < n ? inst[lane] : -1;
     if (g >= n_inst) g = -1;
     const bool act = g >= 0;
     unsigned long long todo = __ballot(act);
@@ -820,7 +822,8 @@ __global__ __launch_bounds__(kBlock) void k_commit(int64_t n, const int* __restr
         const unsigned long long same = __ballot(act && g == gl);
         int base = 0;
         if (lane == leader) {
-            base = atomicAdd(&pend_cnt[gl], __popcll(same));
+            base = pend_cnt[gl];
+            pend_cnt[gl] = base + __popcll(same);
             pend_touched[gl] = 1;
         }
         base = __builtin_amdgcn_readlane(base, leader);
@@ -829,11 +832,65 @@ __global__ __launch_bounds__(kBlock) void k_commit(int64_t n, const int* __restr
     }
     if (act) {
         if (slot < cap) {
-            pend_prompt[(size_t)g * cap + slot] = ctx0[i];
-            pend_len[(size_t)g * cap + slot] = pred_len[i];
+            pend_prompt[(size_t)g * cap + slot] = ctx0[lane];
+            pend_len[(size_t)g * cap + slot] = pred_len[lane];
         } else {
             atomicOr(&counters[0], GR_DEV_ENTRIES_DROPPED);
         }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_commit_mark(int64_t n, const int* __restrict__ inst, int n_inst,
+                                                        int* __restrict__ mark)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const int g = inst[i];
+    if (g >= 0 && g < n_inst) mark[g] = 1;
+}
+
+__global__ __launch_bounds__(kBlock) void k_commit_place(int64_t n, const int* __restrict__ inst,
+                                                         const int* __restrict__ ctx0, const int* __restrict__ pred_len,
+                                                         int* __restrict__ mark, int* __restrict__ pend_cnt,
+                                                         int* __restrict__ pend_prompt, int* __restrict__ pend_len,
+                                                         int* __restrict__ pend_touched, int cap, int n_inst,
+                                                         int* __restrict__ counters)
+{
+    const int lane = lane_id();
+    const int g = blockIdx.x * kBuildWaves + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    if (g >= n_inst || !mark[g]) return;
+    int base = pend_cnt[g];
+    bool dropped = false;
+    constexpr int kStep = 4;      // blocks of 64 requests in flight together
+    for (int64_t i0 = 0; i0 < n; i0 += kStep * kWave) {
+        int gi[kStep];
+#pragma unroll
+        for (int k = 0; k < kStep; ++k) {
+            const int64_t i = i0 + k * kWave + lane;
+            gi[k] = i < n ? inst[i] : -1;
+        }
+#pragma unroll
+        for (int k = 0; k < kStep; ++k) {
+            const unsigned long long m = __ballot(gi[k] == g);
+            if (!m) continue;
+            if (gi[k] == g) {
+                const int64_t i = i0 + k * kWave + lane;
+                const int slot = base + __popcll(m & ((1ull << lane) - 1ull));
+                if (slot < cap) {
+                    pend_prompt[(size_t)g * cap + slot] = ctx0[i];
+                    pend_len[(size_t)g * cap + slot] = pred_len[i];
+                } else {
+                    dropped = true;
+                }
+            }
+            base += __popcll(m);
+        }
+    }
+    if (__ballot(dropped) && lane == 0) atomicOr(&counters[0], GR_DEV_ENTRIES_DROPPED);
+    if (lane == 0) {
+        pend_cnt[g] = base;
+        pend_touched[g] = 1;
+        mark[g] = 0;
     }
 }
 
@@ -851,8 +908,16 @@ void launch_build(const BuildArgs& b, int M, hipStream_t s)
 int launch_commit(gr_fleet* f, int64_t n, const int* inst, const int* ctx0, const int* pred_len, hipStream_t s)
 {
     if (n == 0) return GR_OK;
-    hipLaunchKernelGGL(k_commit, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, n, inst, ctx0, pred_len,
-                       f->pend_cnt, f->pend_prompt, f->pend_len, f->pend_touched, f->cap, f->n_inst, f->counters);
+    if (n <= kWave) {
+        hipLaunchKernelGGL(k_commit_wave, dim3(1), dim3(kWave), 0, s, (int)n, inst, ctx0, pred_len, f->pend_cnt,
+                           f->pend_prompt, f->pend_len, f->pend_touched, f->cap, f->n_inst, f->counters);
+    } else {
+        hipLaunchKernelGGL(k_commit_mark, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, n, inst,
+                           f->n_inst, f->commit_mark);
+        hipLaunchKernelGGL(k_commit_place, dim3((f->n_inst + kBuildWaves - 1) / kBuildWaves), dim3(kBlock), 0, s, n, inst,
+                           ctx0, pred_len, f->commit_mark, f->pend_cnt, f->pend_prompt, f->pend_len, f->pend_touched,
+                           f->cap, f->n_inst, f->counters);
+    }
     return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
 }
 

@@ -159,8 +159,11 @@ def test_tiny_fleet_with_queue_heavy_caps():
         report(f"tiny cap {cap}", parity.run_and_check(fl))
 
 
-def test_feedback_routing_with_batch_caps_request_by_request():
+@pytest.mark.parametrize("chunk,n_req", [(1, 200), (16, 512), (128, 1024), (700, 2100)])
+def test_feedback_routing_with_batch_caps(chunk, n_req):
+    """Under caps the order in which a chunk's requests queue up on an instance shows in every later
+    estimate: it is the order of the batch, as in the reference."""
     fl = workloads.make_fleet(workloads.spec("mid", slo_scale=3.0, seed=54))
     fl.batch_cap = workloads.batch_caps(fl, 0.7, 1.05, seed=4)
-    rep = parity.run_feedback_and_check(fl, 1, n_req=200)
-    report("feedback caps chunk 1", rep)
+    rep = parity.run_feedback_and_check(fl, chunk, n_req=n_req)
+    report(f"feedback caps chunk {chunk}", rep)
