@@ -1139,7 +1139,7 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     // if they are equal, and T >= min) and huge elsewhere; the least key is the earliest such block.
     // That is three instructions of the class that issues two per slot and half a three-way
     // minimum per block, instead of a compare and a select.
-    // A second key of the same kind with the blocks counted down gives the latest such block: the
+    // A second key of the same kind with the block number negated gives the latest such block: the
     // two differ when the lane holds the minimum at more than one position (different instances
     // with the same latency), and then the tie goes to the lowest instance index, one by one.
     int firstB = 0x7fffffff, lastB = -1;
@@ -1147,18 +1147,16 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
         const int lw = s_win & (kWave - 1), half = lane >> 5;
         const float* __restrict__ pe = rv.E + half * kWave + lw;
         const float2* __restrict__ pk = rv.posK + half * kWave + lw;
-        float blk = (float)half, key = 0x1p100f;
-        float back = (float)(rv.nblk - half), keyL = 0x1p100f;
+        float blk = (float)half, key = 0x1p100f, keyL = 0x1p100f;
 #pragma unroll 8
         for (int i = 0; i < rv.nblk / 2; ++i) {       // block 2 i + half
             const float Tc = fmaf(s_c0, kappa_of(pk[i * 2 * kWave], rv.Lf), pe[i * 2 * kWave]);
             const float off = Tc - s_Tm;
             key = fminf(key, fmaf(off, 0x1p100f, blk));
-            keyL = fminf(keyL, fmaf(off, 0x1p100f, back));
+            keyL = fminf(keyL, fmaf(off, 0x1p100f, -blk));     // minus the latest block where T equals the minimum
             blk += 2.0f;
-            back -= 2.0f;
         }
-        if (key < 0x1p30f) { firstB = (int)key; lastB = rv.nblk - (int)keyL; }
+        if (key < 0x1p30f) { firstB = (int)key; lastB = -(int)keyL; }
     }
     firstB = min(firstB, __shfl_xor(firstB, 32, kWave));
     lastB = max(lastB, __shfl_xor(lastB, 32, kWave));
