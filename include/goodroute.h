@@ -84,6 +84,16 @@ enum {
  *   max_len                   upper bound of any remaining / predicted decode length
  *   max_requests              upper bound of n_req of one gr_score_route call
  * Hard limits: max_entries_per_inst <= 2048; max_len <= 32767.
+ * Device memory held by the handle until gr_destroy, all of it allocated here: with
+ * cap = max_entries_per_inst rounded up to 64, 128, .. 2048, M' = n_inst rounded up to a
+ * multiple of 128 and N = max(max_requests, n_inst * max_entries_per_inst),
+ *   18 * n_inst * cap bytes          instance tables and the lists of feedback routing,
+ *   8 * n_inst * max_entries_per_inst bytes   per held request (its instance, a spare finish time),
+ *   4.25 * M' * min(max_len + 1, N) bytes     the per-(distinct length, instance) table of a scoring
+ *                                    pass, reserved for the worst case whatever the batches turn
+ *                                    out to be (285 MB for 4 096 instances and max_len 16 384),
+ *   16.2 * N bytes                   the requests of a scoring pass in grouped order,
+ * plus a few arrays of n_inst or max_len + 1 words.
  */
 int gr_create(gr_fleet** out, int32_t n_inst, int32_t n_class,
               const double* delta, const double* alpha, const double* beta, const double* gamma,
