@@ -168,7 +168,8 @@ int gr_score_route(gr_fleet* f, int64_t n_req,
  * selections of the pass (16 bytes per request) live in a fixed array of 64 KiB in the
  * library's device image instead of the handle's workspace; the call queues three kernels on
  * the stream (one sets the array's slots for this batch; two more, for the capability order,
- * on the first scoring call after a status build) and calls no hipMalloc, hipFree,
+ * on the first scoring call after a status build and whenever the stream is being captured)
+ * and calls no hipMalloc, hipFree,
  * memset, copy or synchronisation.  Every GPU holds one such array for the life of the
  * process and every call on that GPU uses it, whatever the handle: calls that overlap on one
  * GPU (two streams, two threads, two handles) race and must be serialised by the caller.
@@ -275,7 +276,9 @@ int gr_risk_scan(gr_fleet* f,
  *
  *   weight       in [0, 1]
  *   obs_wait, obs_prefill, obs_decode   DEVICE float[n_inst] each; NULL = no new sample of that term
- * The estimates live in the handle, in double precision.
+ * The estimates live in the handle, in double precision.  Tables and capability order of the
+ * last gr_build_status / gr_risk_scan keep the estimates they were built with: new samples show
+ * from the next build on.
  */
 int gr_observe(gr_fleet* f, double weight, const float* obs_wait, const float* obs_prefill,
                const float* obs_decode, void* hip_stream);

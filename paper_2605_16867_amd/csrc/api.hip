@@ -299,6 +299,11 @@ int gr_observe(gr_fleet* f, double weight, const float* obs_wait, const float* o
     if (!f || !(weight >= 0.0 && weight <= 1.0)) return GR_ERR_INVALID_ARG;
     if (!obs_wait && !obs_prefill && !obs_decode) return GR_OK;
     f->tables_current = false;      // (a blended table holds the smoothed status)
+    // the capability order of the current tables carries the prefill estimate as it is now
+    if (f->has_status && !f->ranks_current) {
+        const int rc = launch_ranks(f, nullptr, static_cast<hipStream_t>(hip_stream));
+        if (rc != GR_OK) return rc;
+    }
     return launch_ema(f, weight, obs_wait, obs_prefill, obs_decode, static_cast<hipStream_t>(hip_stream));
 }
 

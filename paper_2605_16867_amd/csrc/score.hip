@@ -1452,6 +1452,15 @@ static int launch_direct(gr_fleet* f, const ReqSrc& src, const ScoreOut& out, un
     return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
 }
 
+// Whether a scoring pass on stream `s` has to make the capability order first.
+static int ranks_needed(const gr_fleet* f, hipStream_t s, bool* needed)
+{
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &capturing) != hipSuccess) return GR_ERR_HIP;
+    *needed = !f->ranks_current || capturing != hipStreamCaptureStatusNone;
+    return GR_OK;
+}
+
 int static_scratch(int device, unsigned long long** out)
 {
     if (device < 0 || device >= kMaxDevices) return GR_ERR_TOO_LARGE;
@@ -1479,7 +1488,9 @@ int launch_score_static(gr_fleet* f, const ReqSrc& src, const ScoreOut& out, hip
     // the call can be recorded into a graph
     hipLaunchKernelGGL(k_fill_ones, dim3((unsigned)((src.n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, best, (int)src.n);
     if (hipGetLastError() != hipSuccess) return GR_ERR_HIP;
-    if (!f->ranks_current) {       // the capability order of the current status (two small kernels, no allocation)
+    bool with_ranks = false;       // the capability order of the current status (two small kernels, no allocation)
+    if (ranks_needed(f, s, &with_ranks) != GR_OK) return GR_ERR_HIP;
+    if (with_ranks) {
         const int rc2 = launch_ranks(f, nullptr, s);
         if (rc2 != GR_OK) return rc2;
     }
@@ -1496,19 +1507,19 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     }
     // up to about two million pairs (the default) a thread per pair is cheaper than the five kernels
     // of the grouped pass
+    // The capability order of the current status, if nobody has made it yet, comes first.  While
+    // the stream is being captured it always does: a recorded pass may be replayed after a status
+    // build that was recorded elsewhere.
+    bool with_ranks = false;
+    if (ranks_needed(f, s, &with_ranks) != GR_OK) return GR_ERR_HIP;
     if (small_batch_ok && !migrate && n <= kDirectMax && n * f->m_pad <= f->small_batch_pairs) {
-        if (!f->ranks_current) {
+        if (with_ranks) {
             const int rc = launch_ranks(f, nullptr, s);
             if (rc != GR_OK) return rc;
         }
         return launch_direct(f, src, out, f->direct_best, s);
     }
-    // The capability order of the current status, if nobody has made it yet, rides along with the
-    // first two launches.  While the stream is being captured it always does: a recorded pass may
-    // be replayed after a status build that was recorded elsewhere.
-    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
-    if (hipStreamIsCapturing(s, &capturing) != hipSuccess) return GR_ERR_HIP;
-    const bool with_ranks = !f->ranks_current || capturing != hipStreamCaptureStatusNone;
+    // In the grouped pass it rides along with the first two launches.
     const RankArgs ranks = rank_args(f, nullptr);
     const int rank_bx = with_ranks ? (f->n_inst + kWave - 1) / kWave : 0;
     const int rank_blocks = rank_bx * ((f->n_inst + kGroupBlock - 1) / kGroupBlock);

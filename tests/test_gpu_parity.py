@@ -87,6 +87,57 @@ def test_blend_with_prefixes_and_exclusions():
     report("mid blend 0.6 + prefixes + exclude", rep)
 
 
+def test_observations_after_a_build_show_from_the_next_build_on():
+    """Samples that arrive between a status build and a routing call change nothing the call
+    sees: tables and capability order keep the estimates they were built with."""
+    import torch
+    dev = "cuda:0"
+    fl = workloads.make_fleet(workloads.spec("mid", slo_scale=2.0, seed=33))
+    d = parity.upload(fl, dev)
+    rounds = workloads.observed_status(fl, 3, seed=6)
+    f32t = lambda x: torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(dev)
+    h = parity.make_handle(fl)
+    for w, ow, op, od in rounds[:2]:
+        h.gr_observe(w, f32t(ow), f32t(op), f32t(od))
+    h.gr_set_blend(0.7)
+    fin = torch.empty(len(fl.act_prompt), dtype=torch.float32, device=dev)
+    n = len(fl.in_prompt)
+
+    def route():
+        inst = torch.full((n,), -7, dtype=torch.int32, device=dev)
+        slack = torch.zeros(n, dtype=torch.float32, device=dev)
+        h.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], inst, slack)
+        torch.cuda.synchronize()
+        return inst.cpu().numpy(), slack.cpu().numpy()
+
+    build = lambda: h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"], d["q_off"],
+                                      d["q_prompt"], d["q_len"], fin)
+    build()
+    w, ow, op, od = rounds[2]
+    h.gr_observe(w, f32t(ow * 3.0), f32t(op * 3.0), f32t(od * 3.0))      # before the first routing call of this build
+    a_inst, a_slack = route()
+    h.gr_observe(w, f32t(ow), f32t(op * 0.2), f32t(od))                  # and between two routing calls
+    b_inst, b_slack = route()
+    assert np.array_equal(a_inst, b_inst) and np.array_equal(a_slack.view(np.uint32), b_slack.view(np.uint32))
+    # the same fleet built after only the first two rounds routes the same way
+    h2 = parity.make_handle(fl)
+    for w2, ow2, op2, od2 in rounds[:2]:
+        h2.gr_observe(w2, f32t(ow2), f32t(op2), f32t(od2))
+    h2.gr_set_blend(0.7)
+    fin2 = torch.empty_like(fin)
+    h2.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"], d["q_off"], d["q_prompt"], d["q_len"], fin2)
+    c_inst = torch.full((n,), -7, dtype=torch.int32, device=dev)
+    c_slack = torch.zeros(n, dtype=torch.float32, device=dev)
+    h2.gr_score_route(d["in_prompt"], d["in_len"], d["in_budget"], c_inst, c_slack)
+    torch.cuda.synchronize()
+    assert np.array_equal(a_inst, c_inst.cpu().numpy()) and np.array_equal(a_slack.view(np.uint32), c_slack.cpu().numpy().view(np.uint32))
+    # after a new build the samples do show
+    build()
+    e_inst, _ = route()
+    assert (e_inst != a_inst).any()
+    h.close(); h2.close()
+
+
 def test_blend_zero_is_the_white_box_model_and_errors():
     from paper_2605_16867_amd import binding
     fl = workloads.make_fleet(workloads.spec("tiny"))
