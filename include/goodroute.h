@@ -314,8 +314,9 @@ int gr_set_blend(gr_fleet* f, double black_box_weight);
  *   cap   HOST int32[n_inst], each >= 1; NULL removes the caps.
  * Host call; waits for the device.
  *
- * With gr_route_feedback, the requests of a chunk queue up on their instances in the order
- * of the batch, whatever the chunk size.
+ * With gr_route_feedback under caps, the requests of a chunk queue up on their instances in
+ * the order of the batch, whatever the chunk size (without caps the order of a queue shows
+ * in no output and is not kept).
  */
 int gr_set_batch_cap(gr_fleet* f, const int32_t* cap);
 

@@ -802,8 +802,11 @@ __global__ __launch_bounds__(kBlock) void k_ema(int n_inst, double w, const floa
 // of earlier requests of the chunk that were sent to the same instance.  That order matters under
 // batch caps (admission is first come, first served), so it must not depend on how the hardware
 // schedules waves.  A chunk that fits one wave is placed by that wave (lanes are in request
-// order).  A larger chunk takes two kernels: the first marks the instances that were chosen at
-// all, the second gives every marked instance a wave that walks the chunk in order.
+// order).  A larger chunk under caps takes two kernels: the first marks the instances that were
+// chosen at all, the second gives every marked instance a wave that walks the chunk in order.
+// Without caps the order of a queue shows in no output (the requests behind it wait for all of
+// them either way; sums and sorted lengths do not depend on it), and a larger chunk is placed by
+// one kernel that hands out slots with one atomic per wave and instance.
 __global__ __launch_bounds__(kWave) void k_commit_wave(int n, const int* __restrict__ inst,
                                                        const int* __restrict__ ctx0, const int* __restrict__ pred_len,
                                                        int* __restrict__ pend_cnt, int* __restrict__ pend_prompt,
@@ -834,6 +837,42 @@ __global__ __launch_bounds__(kWave) void k_commit_wave(int n, const int* __restr
         if (slot < cap) {
             pend_prompt[(size_t)g * cap + slot] = ctx0[lane];
             pend_len[(size_t)g * cap + slot] = pred_len[lane];
+        } else {
+            atomicOr(&counters[0], GR_DEV_ENTRIES_DROPPED);
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_commit_any_order(int64_t n, const int* __restrict__ inst,
+                                                             const int* __restrict__ ctx0, const int* __restrict__ pred_len,
+                                                             int* __restrict__ pend_cnt, int* __restrict__ pend_prompt,
+                                                             int* __restrict__ pend_len, int* __restrict__ pend_touched,
+                                                             int cap, int n_inst, int* __restrict__ counters)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int lane = lane_id();
+    int g = i < n ? inst[i] : -1;
+    if (g >= n_inst) g = -1;
+    const bool act = g >= 0;
+    unsigned long long todo = __ballot(act);
+    int slot = 0;
+    while (todo) {      // many requests of a chunk go to the same instance: one atomic for all of a wave's
+        const int leader = __ffsll((long long)todo) - 1;
+        const int gl = __builtin_amdgcn_readlane(g, leader);
+        const unsigned long long same = __ballot(act && g == gl);
+        int base = 0;
+        if (lane == leader) {
+            base = atomicAdd(&pend_cnt[gl], __popcll(same));
+            pend_touched[gl] = 1;
+        }
+        base = __builtin_amdgcn_readlane(base, leader);
+        if (act && g == gl) slot = base + __popcll(same & ((1ull << lane) - 1ull));
+        todo &= ~same;
+    }
+    if (act) {
+        if (slot < cap) {
+            pend_prompt[(size_t)g * cap + slot] = ctx0[i];
+            pend_len[(size_t)g * cap + slot] = pred_len[i];
         } else {
             atomicOr(&counters[0], GR_DEV_ENTRIES_DROPPED);
         }
@@ -911,6 +950,10 @@ int launch_commit(gr_fleet* f, int64_t n, const int* inst, const int* ctx0, cons
     if (n <= kWave) {
         hipLaunchKernelGGL(k_commit_wave, dim3(1), dim3(kWave), 0, s, (int)n, inst, ctx0, pred_len, f->pend_cnt,
                            f->pend_prompt, f->pend_len, f->pend_touched, f->cap, f->n_inst, f->counters);
+    } else if (!f->has_cap) {
+        hipLaunchKernelGGL(k_commit_any_order, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, n, inst,
+                           ctx0, pred_len, f->pend_cnt, f->pend_prompt, f->pend_len, f->pend_touched, f->cap, f->n_inst,
+                           f->counters);
     } else {
         hipLaunchKernelGGL(k_commit_mark, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, s, n, inst,
                            f->n_inst, f->commit_mark);
