@@ -988,6 +988,7 @@ constexpr int kSparseFeasible = 8;   // up to this many feasible requests of a t
 constexpr int kDenseBlocks = 2;      // blocks looked at for all requests at once before the bounded walk
 
 constexpr int kXcdRun = 8;     // workgroups in a row that stay on one XCD
+constexpr int kSmallTilesFirstBelow = 4 * 256 * 24;   // tiles: four rounds of the chip's 6 waves per SIMD
 
 // One wave per tile: up to kTileReq requests of one length against all
 // instances.  Lane = position in capability order within a block of 64; the
@@ -1029,14 +1030,19 @@ __global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6
     const int seq = blockIdx.x >> 3;
     const int bid = (seq / kXcdRun) * (8 * kXcdRun) + (int)(blockIdx.x & 7) * kXcdRun + seq % kXcdRun;
     if (bid >= groups) return;
-    const int t = bid * kW + wave;
+    // Tiles come cheapest last (the common lengths first, the rare ones with a few requests each at
+    // the end), which lets a launch of many rounds of waves tail off smoothly.  A launch of two or
+    // three rounds is better off the other way round: its small tiles are then done next to the
+    // large ones instead of adding a round of their own, each a chain of dependent loads long.
+    const int idx = bid * kW + wave;
+    const int t = NT < kSmallTilesFirstBelow ? NT - 1 - idx : idx;
     float2* lds_grpK = lds_posK + a.m_pad;      // least (delta, gamma) of each run of kMemoP positions
     if (kLdsK) {
         for (int p = threadIdx.x; p < a.m_pad; p += kW * kWave) lds_posK[p] = a.posK[p];
         for (int g = threadIdx.x; g < a.m_pad / kMemoP; g += kW * kWave) lds_grpK[g] = a.grp_k[g];
         __syncthreads();
     }
-    if (t >= NT) return;
+    if (idx >= NT) return;
 
     const int u = a.tile_row[t];        // (written by the memo kernel)
     // The row's requests are dealt out to its tiles in turn (request q of the row goes to tile
