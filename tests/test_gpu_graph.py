@@ -81,3 +81,58 @@ def test_replays_equal_direct_calls(name, small_batch_pairs):
         assert int(o_graph["nfl"].item()) == int(o_graph["flag"].sum().item())
     h_graph.close()
     h_direct.close()
+
+
+@pytest.mark.parametrize("entry,small_batch_pairs", [("gr_score_route", None), ("gr_score_route", 0),
+                                                     ("gr_score_route_noalloc", None)])
+def test_a_recorded_routing_call_follows_status_builds_made_outside_the_graph(entry, small_batch_pairs):
+    """Only the routing call is recorded; the status is rebuilt by direct calls between replays.
+    A recorded scoring pass makes the capability order of whatever status it finds."""
+    import torch
+    dev = "cuda:0"
+    fleets = [workloads.make_fleet(workloads.spec("mid", seed=s, slo_scale=sc, n_incoming=1024))
+              for s, sc in ((0, 2.0), (1, 3.0), (2, 8.0))]
+    ups = [parity.upload(fl, dev) for fl in fleets]
+    na, R = len(fleets[0].act_prompt), len(fleets[0].in_prompt)
+    parity.SMALL_BATCH_PAIRS = small_batch_pairs
+    try:
+        h_graph, h_direct = parity.make_handle(fleets[0]), parity.make_handle(fleets[0])
+    finally:
+        parity.SMALL_BATCH_PAIRS = None
+    d = {k: v.clone() for k, v in ups[0].items()}
+    o_graph, o_direct = _outputs(torch, na, R, dev), _outputs(torch, na, R, dev)
+
+    def build(h, src, o):
+        h.gr_build_status(src["act_off"], src["act_prompt"], src["act_gen"], src["act_rem"],
+                          src["q_off"], src["q_prompt"], src["q_len"], o["fin"])
+
+    def route(h, src, o):
+        getattr(h, entry)(src["in_prompt"], src["in_len"], src["in_budget"], o["inst"], o["slack"], out_fallback=o["fb"])
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        build(h_graph, d, o_graph)
+        route(h_graph, d, o_graph)            # the capability order of this status now exists
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        route(h_graph, d, o_graph)
+
+    for rep, up in enumerate(ups[1:] + ups[:1]):
+        for k in INPUTS:
+            d[k].copy_(up[k])
+        for k in ("inst", "slack", "fb"):
+            o_graph[k].fill_(7)
+        build(h_graph, d, o_graph)            # a direct call: another status, another capability order
+        graph.replay()
+        build(h_direct, up, o_direct)
+        route(h_direct, up, o_direct)
+        torch.cuda.synchronize()
+        for k in ("fin", "inst", "slack", "fb"):
+            a, b = o_graph[k].cpu().numpy(), o_direct[k].cpu().numpy()
+            assert np.array_equal(a, b, equal_nan=a.dtype.kind == "f"), f"replay {rep}: {k} differs from the direct call"
+    assert len({tuple(workloads.make_fleet(workloads.spec("mid", seed=s)).act_rem[:8]) for s in (0, 1, 2)}) == 3
+    h_graph.close()
+    h_direct.close()
