@@ -28,5 +28,18 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+PROBE = os.path.join(CSRC, "probe_valu_issue")
+
+
+def build_probe(verbose: bool = False) -> str:
+    """The stand-alone microbenchmark behind the vector-ALU issue model (not part of the library)."""
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-o", PROBE, PROBE + ".hip"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return PROBE
+
+
 if __name__ == "__main__":
     build_library(verbose=True)
+    build_probe(verbose=True)
