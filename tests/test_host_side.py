@@ -149,3 +149,27 @@ def test_exact_ties_are_decided_and_go_to_the_lowest_index():
         assert robust.all() and robust_m.all() and np.array_equal(want, ref.inst)
         assert np.all(band.equal[tie] == 2) and np.all(band.equal[~tie] == 1)
         assert fine == bool(np.all(picked[tight & tie] == want[tight & tie]))
+
+
+def test_recorded_traffic_is_only_reported_for_unchanged_kernel_sources(tmp_path, monkeypatch):
+    """bench.py takes the dominant kernel's HBM bytes from a counter summary under profiles/; the
+    record carries the hash of the kernel sources and is dropped as soon as they differ."""
+    import bench
+    prof = tmp_path / "profiles"
+    prof.mkdir()
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    for rel in bench.KERNEL_SOURCES:
+        path = tmp_path / rel
+        path.parent.mkdir(parents=True, exist_ok=True)
+        path.write_text("// " + rel + "\n")
+    good = bench.sources_sha256()
+    (prof / "heavy_step_all_kernels.md").write_text(
+        "# summary\n\ntraffic-record: kernel=k_tile<migrate> fetch_bytes=100 write_bytes=23 sources_sha256=" + good + "\n"
+        "traffic-record: kernel=k_tile<route> fetch_bytes=7 write_bytes=1 sources_sha256=" + good + "\n")
+    assert bench.recorded_traffic("heavy", "k_tile<migrate>") == (123, os.path.join("profiles", "heavy_step_all_kernels.md"))
+    assert bench.recorded_traffic("heavy", "k_tile<route>")[0] == 8
+    assert bench.recorded_traffic("heavy", "k_build")[0] is None           # no record for that kernel
+    assert bench.recorded_traffic("large", "k_tile<route>")[0] is None     # no summary for that workload
+    (tmp_path / bench.KERNEL_SOURCES[0]).write_text("// edited\n")
+    value, why = bench.recorded_traffic("heavy", "k_tile<migrate>")
+    assert value is None and "changed" in why
