@@ -288,6 +288,7 @@ __device__ inline void rank_final_item(const RankArgs& a, int g)
     if (g < a.n_inst) {
         const int r = a.rank_acc[g];
         a.rank_acc[g] = 0;
+        if ((unsigned)r >= (unsigned)a.n_inst) return;      // (counts are below n_inst by construction; never index past the tables)
         const ClassCoef cc = a.cls[a.inst_class[g]];
         a.rank[g] = r;
         a.order[r] = g;
