@@ -317,12 +317,15 @@ def test_cached_prefixes_decide_when_prefill_dominates():
     assert rep["route_moved_by_hits"] > n // 10
 
 
-def _random_case(rng):
+def _random_case(rng, larger=False):
     """A small fleet with everything drawn at random: size, classes and their
     coefficients, occupancy (idle instances included), queues, the mix of
     lengths of the incoming batch, deadline scale, and which of the optional
     inputs (exclusions, cached prefixes, observed status + blend, batch caps)
-    are present."""
+    are present.  ``larger``: up to 2 050 instances, up to 2 040 held requests
+    per instance (every sort width), up to 9 000 incoming requests."""
+    if larger:
+        return _random_larger_case(rng)
     M = int(rng.choice([1, 2, 3, 17, 64, 65, 130, 300]))
     n_class = int(rng.integers(1, 6))
     classes = [(2e-5 * f, 0.012 * f, 2e-4 * f, 2e-8 * f) for f in rng.uniform(0.5, 6.0, n_class)]
@@ -341,7 +344,34 @@ def _random_case(rng):
     bud = rng.uniform(0.3, 3, R) * float(rng.choice([0.5, 3, 20, 300])) * solo(inc[:, 0], inc[:, 1], c0)
     special = rng.random(R)
     bud = np.where(special < 0.03, 0.0, np.where(special < 0.06, np.inf, np.where(special < 0.08, -1.0, bud)))
-    fl = fleet(rng.integers(0, n_class, M), acts, queued, inc, bud, classes=classes, max_len=max_len)
+    return _finish_random_case(rng, fleet(rng.integers(0, n_class, M), acts, queued, inc, bud, classes=classes,
+                                          max_len=max_len))
+
+
+def _random_larger_case(rng):
+    M = int(rng.choice([63, 64, 65, 127, 129, 256, 257, 511, 1000, 1025, 2050]))
+    n_class = int(rng.integers(1, 7))
+    classes = [(2e-5 * f, 0.012 * f, 2e-4 * f, 2e-8 * f) for f in rng.uniform(0.5, 6.0, n_class)]
+    max_len = int(rng.choice([64, 4096, 32767]))
+    top = int(rng.choice([10, 64, 65, 129, 300, 513, 1100, 2040] if M <= 300 else [10, 70, 130, 260]))
+    occ = rng.integers(0, top + 1, M) * (rng.random(M) > 0.1)
+    acts = [np.stack([rng.integers(1, 3000, n), rng.integers(0, 300, n),
+                      np.clip(np.rint(rng.lognormal(rng.uniform(1, 6), 1, n)), 1, max_len)], 1) if n else np.zeros((0, 3))
+            for n in occ]
+    queued = [[(int(p), int(l)) for p, l in zip(rng.integers(1, 3000, n), rng.integers(1, min(max_len, 500) + 1, n))]
+              for n in np.minimum(rng.integers(0, int(rng.choice([0, 6, 40])) + 1, M) * (rng.random(M) > 0.5), 2048 - occ)]
+    R = min(int(rng.choice([1, 31, 33, 200, 700, 3000, 9000])), (1 << 24) // M)
+    pool = np.clip(np.rint(rng.lognormal(rng.uniform(1, 6), 1.2, int(rng.choice([1, 3, 40, R])))), 1, max_len)
+    inc = np.stack([rng.integers(1, 4000, R), rng.choice(pool, R)], 1)
+    bud = rng.uniform(0.3, 3, R) * float(rng.choice([0.5, 3, 20, 300])) * solo(inc[:, 0], inc[:, 1], classes[0])
+    special = rng.random(R)
+    bud = np.where(special < 0.03, 0.0, np.where(special < 0.06, np.inf, np.where(special < 0.08, -1.0, bud)))
+    return _finish_random_case(rng, fleet(rng.integers(0, n_class, M), acts, queued, inc, bud, classes=classes,
+                                          max_len=max_len))
+
+
+def _finish_random_case(rng, fl):
+    M, R, max_len = len(fl.inst_class), len(fl.in_prompt), fl.max_len
     fl.n_inst = M
     sim = oracle.simulate(fl)
     fl.act_budget = (sim.act_finish * rng.uniform(0.6, 1.4, len(sim.act_finish))).astype(np.float32)
@@ -368,6 +398,18 @@ def test_random_small_fleets(seed):
               f"entries={len(fl.act_prompt)}+{len(fl.q_prompt)} options={sorted(kw)} "
               f"cap={getattr(fl, 'batch_cap', None) is not None}", flush=True)
         parity.run_and_check(fl, seed=seed, **kw)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_random_larger_fleets(seed):
+    rng = np.random.default_rng(2000 + seed)
+    for case in range(10):
+        fl, kw = _random_case(rng, larger=True)
+        print(f"seed {seed} case {case}: M={len(fl.inst_class)} R={len(fl.in_prompt)} "
+              f"entries={len(fl.act_prompt)}+{len(fl.q_prompt)} most per instance "
+              f"{int(max(np.diff(fl.act_off) + np.diff(fl.q_off)))} options={sorted(kw)} "
+              f"cap={getattr(fl, 'batch_cap', None) is not None}", flush=True)
+        parity.run_and_check(fl, seed=seed, sample=2000 if "blackbox" in kw else None, **kw)
 
 
 @pytest.mark.parametrize("capped", [False, True])
