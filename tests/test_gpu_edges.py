@@ -148,6 +148,32 @@ def test_wide_fleets(n_inst):
     assert rep["finish_rel_err"] < 1e-6
 
 
+@pytest.mark.parametrize("n_inst,most", [(1024, 200), (1025, 200), (2048, 200), (2049, 200), (1024, 64), (500, 2048)])
+def test_instances_that_share_waves(n_inst, most):
+    """The status build gives an instance one, two or four waves depending on the fleet's size
+    (four up to 1 024 instances, two up to 2 048) and on how many sort words a lane holds: the
+    sizes either side of each switch, instances that fill their waves exactly, idle ones, queues
+    that straddle the waves, and a routing with feedback on top (the rebuilds read the lists of
+    routed requests the same way)."""
+    rng = np.random.default_rng(n_inst + most)
+    occ = rng.integers(0, most + 1, n_inst)
+    occ[:4] = [most, most - 1, 0, 1]
+    qn = np.minimum(rng.integers(0, 9, n_inst) * (rng.random(n_inst) > 0.5), most - occ)
+    acts = [rand_entries(rng, int(n)) for n in occ]
+    queued = [[(int(p), int(l)) for p, l in zip(rng.integers(1, 3000, n), rng.integers(1, 400, n))] for n in qn]
+    cls = rng.integers(0, 3, n_inst)
+    inc = np.stack([rng.integers(128, 2049, 200), rng.choice([3, 50, 51, 400, 2000], 200)], 1)
+    fl = fleet(cls, acts, queued, inc, rng.uniform(0.8, 3, 200) * solo(inc[:, 0], inc[:, 1]))
+    fl.n_inst = n_inst
+    sim = oracle.simulate(fl)
+    fl.act_budget = (sim.act_finish * rng.uniform(0.5, 1.5, len(sim.act_finish))).astype(np.float32)
+    fl.act_rem_refreshed = np.clip(np.rint(fl.act_rem * rng.lognormal(0, 0.4, len(fl.act_rem))), 1, 4096).astype(np.int32)
+    rep = parity.run_and_check(fl)
+    assert rep["finish_rel_err"] < 1e-6
+    if most < 2048:
+        parity.run_feedback_and_check(fl, chunk=16, n_req=48)
+
+
 def test_batch_cap_departures_in_groups():
     """Full batches whose departures come in groups of equal lengths: the one that
     makes room for a newcomer takes its whole group along (down to an empty batch),
