@@ -32,17 +32,16 @@ static __device__ __align__(256) unsigned long long scratch[2 * gr::kDirectMax];
 namespace gr {
 namespace {
 
+// Length of request i (0 <= i < s.n) and whether it takes part (a migration pass scores the flagged
+// requests only).  Both reads are in bounds whatever the flag says, so neither waits for the other,
+// and a caller that reads several requests has all its loads in flight together.
 template <bool kMigrate>
-__device__ inline bool fetch_len(const ReqSrc& s, int64_t i, int max_len, int& L)
+__device__ __forceinline__ bool fetch_len(const ReqSrc& s, int64_t i, int max_len, int& L)
 {
-    if (kMigrate) {
-        if (!s.flag[i]) return false;
-        L = s.act_rem[i];
-    } else {
-        L = s.pred_len[i];
-    }
-    L = min(max(L, 0), max_len);
-    return true;
+    const int raw = kMigrate ? s.act_rem[i] : s.pred_len[i];
+    const bool takes_part = !kMigrate || s.flag[i] != 0;
+    L = min(max(raw, 0), max_len);
+    return takes_part;
 }
 
 // ------------------------------------------------------------------ grouping by length
@@ -213,46 +212,63 @@ __device__ __forceinline__ void scatter_block(const ScatterArgs& a, int block, i
     for (int L = block * kGroupBlock + tid; L < bins; L += blocks * kGroupBlock) len_cnt[L] = 0;
     __syncthreads();
     const int64_t base = (int64_t)block * (kGroupBlock * kItems);
-    int Ls[kItems];
+    // Everything a request's record needs is read up front, all requests of the thread together (an
+    // index past the batch reads the last request and is dropped below): the reads are in flight
+    // while the slots are counted and reserved.
+    int Ls[kItems], c0s[kItems], pexs[kItems];
+    float Ds[kItems];
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
-        const int64_t i = base + it * kGroupBlock + tid;
-        int L = -1;
-        if (i < s.n) {
-            if (fetch_len<kMigrate>(s, i, max_len, L)) {
-                atomicAdd(&slot[L], 1);
-            } else {
-                L = -1;
-                out_inst[i] = -1;       // not flagged: no migration target
-                out_slack[i] = 0.f;
-            }
+        const int64_t i = base + it * kGroupBlock + tid, ic = min(i, s.n - 1);
+        int L;
+        const bool takes_part = fetch_len<kMigrate>(s, ic, max_len, L);
+        Ls[it] = i < s.n ? (takes_part ? L : -2) : -1;       // -2: in the batch, not scored
+        int ex;
+        if (kMigrate) {
+            c0s[it] = s.act_prompt[ic] + s.act_gen[ic]; Ds[it] = s.act_budget[ic]; ex = s.act_inst[ic];
+        } else {
+            c0s[it] = s.ctx0[ic]; Ds[it] = s.budget[ic]; ex = s.exclude ? s.exclude[ic] : -1;
         }
-        Ls[it] = L;
+        pexs[it] = ex;
     }
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {     // the excluded instance as a position in capability order
+        const int ex = pexs[it];
+        const int r = rank[min(max(ex, 0), n_inst - 1)];
+        pexs[it] = (ex >= 0 && ex < n_inst) ? r : -1;
+    }
+#pragma unroll
+    for (int it = 0; it < kItems; ++it)
+        if (Ls[it] >= 0) atomicAdd(&slot[Ls[it]], 1);
     __syncthreads();
-    for (int L = tid; L < bins; L += kGroupBlock) {
-        const int c = slot[L];
-        if (c) slot[L] = atomicAdd(&len_base[L], c);
+    // one global atomic per length the workgroup has seen, eight of a thread's in flight together
+    constexpr int kAhead = 8;
+    for (int L0 = tid; L0 < bins; L0 += kAhead * kGroupBlock) {
+        int c[kAhead], b[kAhead];
+#pragma unroll
+        for (int k = 0; k < kAhead; ++k) {
+            const int L = L0 + k * kGroupBlock;
+            c[k] = L < bins ? slot[L] : 0;
+        }
+#pragma unroll
+        for (int k = 0; k < kAhead; ++k) b[k] = c[k] ? atomicAdd(&len_base[L0 + k * kGroupBlock], c[k]) : 0;
+#pragma unroll
+        for (int k = 0; k < kAhead; ++k)
+            if (c[k]) slot[L0 + k * kGroupBlock] = b[k];
     }
     __syncthreads();
 #pragma unroll
     for (int it = 0; it < kItems; ++it) {
         const int L = Ls[it];
-        if (L < 0) continue;
         const int64_t i = base + it * kGroupBlock + tid;
-        const int pos = atomicAdd(&slot[L], 1);
-        int c0, ex;
-        float D;
-        if (kMigrate) {
-            c0 = s.act_prompt[i] + s.act_gen[i]; D = s.act_budget[i]; ex = s.act_inst[i];
-        } else {
-            c0 = s.ctx0[i]; D = s.budget[i]; ex = s.exclude ? s.exclude[i] : -1;
+        if (L >= 0) {
+            ReqRec r;
+            r.c0 = (float)c0s[it]; r.D = Ds[it]; r.pex = pexs[it]; r.orig = (int)i;
+            recs[atomicAdd(&slot[L], 1)] = r;
+        } else if (L == -2) {
+            out_inst[i] = -1;       // not flagged: no migration target
+            out_slack[i] = 0.f;
         }
-        ReqRec r;
-        r.c0 = (float)c0; r.D = D;
-        r.pex = (ex >= 0 && ex < n_inst) ? rank[ex] : -1;
-        r.orig = (int)i;
-        recs[pos] = r;
     }
 }
 
@@ -1530,10 +1546,14 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
     const int rank_bx = with_ranks ? (f->n_inst + kWave - 1) / kWave : 0;
     const int rank_blocks = rank_bx * ((f->n_inst + kGroupBlock - 1) / kGroupBlock);
     const int bins = f->bins;
-    // requests per workgroup of the grouping kernels.  Every workgroup pays a pass over all length
-    // bins and one global atomic per length it has seen: the histogram of a large batch is faster
-    // with few large workgroup shares, the scatter (which also writes the records) is not.
-    const int h_items = n > (int64_t(1) << 20) ? 16 : 4, s_items = n > (int64_t(1) << 20) ? 8 : 4;
+    // Requests per thread of the grouping kernels.  Every workgroup pays a pass over all length
+    // bins and one global atomic per length it has seen, so the histogram of a large batch is
+    // faster with few large workgroup shares.  The scatter keeps what it has read of its requests
+    // in registers until their slots are known: four requests per thread leave room for two
+    // workgroups on a compute unit (with eight, the tabulating workgroups that share its launch
+    // lose more than the scatter gains: 80 against 62 us on 2.1 M requests).
+    const int h_items = n > (int64_t(1) << 20) ? 16 : 4;
+    constexpr int kScatterItems = 4;
     const auto blocks_for = [n](int items) {
         return (unsigned)((n + (int64_t)kGroupBlock * items - 1) / ((int64_t)kGroupBlock * items));
     };
@@ -1574,8 +1594,8 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         const size_t memo_lds = memo_lds_bytes(f), lds = scat_lds > memo_lds ? scat_lds : memo_lds;
         ProfScope ps(f, kGroupRoute + off, s);
 #define GR_LAUNCH_GROUP(M, I) hipLaunchKernelGGL((k_group<M, I>), dim3(gx * gy + blocks_for(I)), dim3(kGroupBlock), lds, s, sc, m, gx, gy)
-        if (migrate) { if (s_items == 8) GR_LAUNCH_GROUP(true, 8); else GR_LAUNCH_GROUP(true, 4); }
-        else { if (s_items == 8) GR_LAUNCH_GROUP(false, 8); else GR_LAUNCH_GROUP(false, 4); }
+        if (migrate) GR_LAUNCH_GROUP(true, kScatterItems);
+        else GR_LAUNCH_GROUP(false, kScatterItems);
 #undef GR_LAUNCH_GROUP
     }
     {
