@@ -1445,8 +1445,7 @@ int score_prepare(gr_fleet*)
     constexpr size_t group = scat > memo ? scat : memo;
     const bool ok = set_lds(k_hist<false, 4>, hist) && set_lds(k_hist<true, 4>, hist) &&
                     set_lds(k_hist<false, 16>, hist) && set_lds(k_hist<true, 16>, hist) &&
-                    set_lds(k_group<false, 4>, group) && set_lds(k_group<true, 4>, group) &&
-                    set_lds(k_group<false, 8>, group) && set_lds(k_group<true, 8>, group);
+                    set_lds(k_group<false, 4>, group) && set_lds(k_group<true, 4>, group);
     return ok ? GR_OK : GR_ERR_HIP;
 }
 
