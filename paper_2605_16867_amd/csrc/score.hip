@@ -1031,10 +1031,11 @@ constexpr int kSmallTilesFirstBelow = 4 * 256 * 24;   // tiles: four rounds of t
 // walk): 24 / kW workgroups of m_pad * 8.5 bytes share a compute unit, and the
 // texture path is left to the table rows and the gathers of the search for the
 // minimum.
-template <bool kWriteT, int kW>
-__global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(6, 6))) void k_tile(TileArgs a)
+template <bool kWriteT, int kW, int kWavesPerSimd>
+__global__ __launch_bounds__(kW * kWave) __attribute__((amdgpu_waves_per_eu(kWavesPerSimd, kWavesPerSimd))) void k_tile(TileArgs a)
 {
-    constexpr bool kLdsK = kW > 4;
+    // (four waves per workgroup at six per SIMD is the variant without the LDS copy)
+    constexpr bool kLdsK = kW > 4 || kWavesPerSimd > 6;
     extern __shared__ float2 lds_posK[];
     const int lane = lane_id();
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -1607,17 +1608,23 @@ int launch_score(gr_fleet* f, const ReqSrc& src, bool migrate, const ScoreOut& o
         // 24 waves per compute unit (6 per SIMD): the coefficient pairs go to LDS when the
         // 24 / kW workgroups resident together have room for a copy each
         const size_t k_bytes = (size_t)(f->m_pad + f->m_pad / kMemoP) * sizeof(float2);
-        // (12 waves per workgroup measured 1 % faster than 8 at 4 096 instances, 4 % slower at 1 024)
-        const int kw = k_bytes <= 24576 ? 8 : k_bytes <= 65536 ? 12 : 4;
-        unsigned blocks = (unsigned)((max_tiles + kw - 1) / kw);
+        // (12 waves per workgroup measured 1 % faster than 8 at 4 096 instances, 4 % slower at 1 024.
+        // Up to 1 024 instances seven copies fit as well: workgroups of 4 waves at 7 waves per SIMD --
+        // a few registers of each lane then live in scratch memory -- are 3 % faster at 1 024
+        // instances, where the short rows leave the vector ALU idle a fifth of the time at 6, and
+        // 5 % slower at 256, where a tile is a chain of dependent loads and little else.)
+        const int kw = (f->m_pad >= 512 && k_bytes <= 8704) ? 7 : k_bytes <= 24576 ? 8 : k_bytes <= 65536 ? 12 : 4;
+        const int wg = kw == 7 ? 4 : kw;              // waves per workgroup
+        unsigned blocks = (unsigned)((max_tiles + wg - 1) / wg);
         blocks = (blocks + 8u * kXcdRun - 1) / (8u * kXcdRun) * (8u * kXcdRun);
         ProfScope ps(f, kTileRoute + off, s);
-#define GR_LAUNCH_TILE(W, L) \
-        if (out.T) hipLaunchKernelGGL((k_tile<true, W>), dim3(blocks), dim3(W * kWave), L, s, t); \
-        else hipLaunchKernelGGL((k_tile<false, W>), dim3(blocks), dim3(W * kWave), L, s, t)
-        if (kw == 8) { GR_LAUNCH_TILE(8, k_bytes); }
-        else if (kw == 12) { GR_LAUNCH_TILE(12, k_bytes); }
-        else { GR_LAUNCH_TILE(4, 0); }
+#define GR_LAUNCH_TILE(W, E, L) \
+        if (out.T) hipLaunchKernelGGL((k_tile<true, W, E>), dim3(blocks), dim3(W * kWave), L, s, t); \
+        else hipLaunchKernelGGL((k_tile<false, W, E>), dim3(blocks), dim3(W * kWave), L, s, t)
+        if (kw == 7) { GR_LAUNCH_TILE(4, 7, k_bytes); }
+        else if (kw == 8) { GR_LAUNCH_TILE(8, 6, k_bytes); }
+        else if (kw == 12) { GR_LAUNCH_TILE(12, 6, k_bytes); }
+        else { GR_LAUNCH_TILE(4, 6, 0); }
 #undef GR_LAUNCH_TILE
     }
     return hipGetLastError() == hipSuccess ? GR_OK : GR_ERR_HIP;
